@@ -1,0 +1,169 @@
+/*
+ * ganq.h - C ABI of the MI355X (gfx950) GANQ per-layer solver.
+ *
+ * GANQ (arXiv 2501.12956) quantises one linear layer W (m x n, m output
+ * channels) to a per-row codebook T (m x 2^N) and an index matrix Q (m x n)
+ * by minimising |W X - W~ X|_F^2, W~_ij = T_i[Q_ij] (Eq. (1)), for
+ * calibration activations X (n x p).  Algorithm 1 alternates a
+ * column-sequential assignment update on the Cholesky factor of H = X X^T
+ * with a closed-form per-row least-squares codebook update.
+ *
+ * Conventions for every call
+ *   - Every array pointer is a DEVICE pointer owned by the caller unless the
+ *     parameter name ends in _host.  The library never frees or keeps a
+ *     caller pointer past the call.
+ *   - Matrices are row-major with an explicit leading dimension in elements.
+ *   - Work is enqueued on the context's HIP stream.  Calls that return a host
+ *     scalar (info_host, loss_host, loss_history_host) synchronise that
+ *     stream before returning; all others are asynchronous.
+ *   - Scratch memory comes from a caller-provided workspace
+ *     (ganq_workspace_bytes / ganq_set_workspace); the library allocates no
+ *     device memory.
+ *   - Errors are returned as ganq_status; nothing aborts or throws across the
+ *     ABI.  Argument checks run on the host before any GPU work.
+ *   - nbits in [1, 4]; C = 2^nbits codes per row.  3 and 4 are the paper's
+ *     settings (Section 4.1), 1 and 2 exist for brute-force tests.
+ */
+#ifndef GANQ_H
+#define GANQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ganq_ctx ganq_ctx; /* opaque: one HIP device + one stream + workspace */
+
+typedef enum {
+  GANQ_OK = 0,
+  GANQ_ERR_INVALID_ARG = 1,
+  GANQ_ERR_UNSUPPORTED = 2,
+  GANQ_ERR_NOT_PD = 3,     /* a Cholesky pivot was <= 0 or not finite */
+  GANQ_ERR_WORKSPACE = 4,  /* workspace missing or too small */
+  GANQ_ERR_HIP = 5         /* HIP runtime failure; text in ganq_last_error */
+} ganq_status;
+
+typedef enum { GANQ_F16 = 0, GANQ_F32 = 1 } ganq_dtype;
+
+/* Which matrix is factorised (Eq. (10), Remark 3.1, Appendix A Eq. (23)-(24)). */
+typedef enum {
+  GANQ_PRECOND_NONE = 0,    /* H */
+  GANQ_PRECOND_LAMBDA = 1,  /* H + lambda I */
+  GANQ_PRECOND_DIAGDOM = 2, /* H + Diag(delta), delta_i = max(sum_j|H_ij| - 2 H_ii, 1e-8) */
+  GANQ_PRECOND_AUTO = 3     /* NONE, and DIAGDOM if a pivot fails */
+} ganq_precond;
+
+/* Rule for the initial codebook T^0 (an input of Algorithm 1 the paper leaves open). */
+typedef enum {
+  GANQ_INIT_QUANTILE_MID = 0,       /* level s at row quantile (s + 1/2)/C, linear interpolation */
+  GANQ_INIT_QUANTILE_ENDPOINTS = 1, /* level s at row quantile s/(C - 1) */
+  GANQ_INIT_MINMAX_GRID = 2         /* C equally spaced values from row min to row max */
+} ganq_init;
+
+/* Value given to a code that no column of the row uses (Eq. (7), pseudo-inverse). */
+typedef enum {
+  GANQ_EMPTY_ZERO = 0, /* 0, the literal Moore-Penrose result */
+  GANQ_EMPTY_KEEP = 1  /* keep the previous codebook entry */
+} ganq_empty;
+
+typedef struct {
+  ganq_precond precond; /* used when ganq_quantize_layer factors H itself */
+  float lambda;         /* for GANQ_PRECOND_LAMBDA */
+  ganq_init init;       /* used when init_codebooks != 0 */
+  int init_codebooks;   /* 0: T holds T^0 on entry; 1: build T^0 from W */
+  ganq_empty empty;
+  int reserved;         /* must be 0 */
+} ganq_options;
+
+/* ---- context ------------------------------------------------------------ */
+
+/* Creates a context bound to HIP device `device` and to `hip_stream`
+ * (a hipStream_t, NULL = the default stream).  Touches no GPU state until the
+ * first compute call.  *out is set to NULL on failure. */
+ganq_status ganq_create(ganq_ctx** out, int device, void* hip_stream);
+ganq_status ganq_destroy(ganq_ctx* ctx);
+
+/* Bytes of workspace that any call on a layer of this shape may need
+ * (p_tokens = 0 when ganq_build_hessian is not used).  0 on invalid input. */
+size_t ganq_workspace_bytes(int64_t m, int64_t n, int64_t p_tokens, int nbits);
+
+/* Hands the context a caller-owned device buffer (256-byte aligned).  It must
+ * stay valid until replaced or the context is destroyed. */
+ganq_status ganq_set_workspace(ganq_ctx* ctx, void* dev_ptr, size_t bytes);
+
+const char* ganq_status_string(ganq_status s);
+/* Text of the last error on this context ("" if none); valid until the next call. */
+const char* ganq_last_error(const ganq_ctx* ctx);
+
+/* ---- the seven calls of the hot path ---------------------------------------- */
+
+/* H = X X^T (Algorithm 1; Eq. (9)).  X is n x p (features x tokens) with
+ * leading dimension ldx >= p, fp16 or fp32 storage (fp32 input is rounded to
+ * fp16 for the matrix-core product; accumulation is fp32).  H is n x n fp32,
+ * both triangles written.  accumulate != 0 adds to the H already there
+ * (streaming token chunks).  Requires p % 8 == 0 and ldx % 8 == 0 for fp16. */
+ganq_status ganq_build_hessian(ganq_ctx* ctx, const void* X, ganq_dtype x_dtype, int64_t n,
+                               int64_t p, int64_t ldx, float* H, int64_t ldh, int accumulate);
+
+/* L = lower Cholesky factor of H (or of its preconditioned form), Eq. (10),
+ * Remark 3.1, Appendix A.  L is n x n fp32 with the strict upper triangle
+ * zeroed; L may not alias H.  *info_host: 0 on success, k > 0 if pivot k
+ * (1-based) was <= 0 or not finite (status GANQ_ERR_NOT_PD; L is then
+ * unspecified).  Under GANQ_PRECOND_AUTO a failed plain attempt is repeated
+ * with DIAGDOM and *info_host reports the second attempt.  Synchronises. */
+ganq_status ganq_cholesky(ganq_ctx* ctx, const float* H, int64_t n, int64_t ldh,
+                          ganq_precond precond, float lambda, float* L, int64_t ldl,
+                          int64_t* info_host);
+
+/* T^0 from per-row quantiles of W (input of Algorithm 1).  T is m x 2^nbits
+ * fp32 row-major, ascending within each row. */
+ganq_status ganq_init_codebooks(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype, int64_t m,
+                                int64_t n, int64_t ldw, int nbits, ganq_init init, float* T);
+
+/* S-update, Eq. (13)-(22) and the inner loop of Algorithm 1: for j = n-1..0
+ * and every row i, Q_ij = argmin_s |W_ij + (sum_{u>j} r_iu L_uj)/L_jj - T_is|
+ * with r_iu = W_iu - T_i[Q_iu]; ties go to the lowest s.  W m x n fp32,
+ * L n x n fp32 lower triangular with positive diagonal, T m x 2^nbits fp32,
+ * Q m x n uint8 (one index per byte).  E (optional, may be NULL) receives the
+ * residuals W - T[Q], m x n fp32 with leading dimension lde. */
+ganq_status ganq_update_S(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                          const float* L, int64_t ldl, const float* T, int nbits, uint8_t* Q,
+                          int64_t ldq, float* E, int64_t lde);
+
+/* T-update, Eq. (4)-(7): T_i = W_i H S_i^T (S_i H S_i^T)^dagger for every
+ * row, S_i the one-hot form of Q_i.  H is the raw X X^T (n x n fp32,
+ * symmetric; both triangles are read).  T holds T^k on entry (used only by
+ * GANQ_EMPTY_KEEP) and T^{k+1} on return.  empty_count (optional, m int32)
+ * receives the number of unused or numerically dependent codes per row. */
+ganq_status ganq_update_T(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                          const float* H, int64_t ldh, const uint8_t* Q, int64_t ldq, int nbits,
+                          ganq_empty empty, float* T, int32_t* empty_count);
+
+/* Objective of Eq. (1) in the form of Eq. (9): sum_i E_i H E_i^T with
+ * E = W - T[Q].  *loss_host receives the total (float64 reduction of fp32
+ * row values); row_loss (optional, m fp32, device) the per-row values.
+ * Synchronises. */
+ganq_status ganq_layer_loss(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                            const float* H, int64_t ldh, const float* T, const uint8_t* Q,
+                            int64_t ldq, int nbits, double* loss_host, float* row_loss);
+
+/* Algorithm 1 given H: optional factorisation (L == NULL: factor H here with
+ * opts->precond), optional T^0 (opts->init_codebooks), then `iters`
+ * alternations of S-update and T-update.  W is m x n fp16 or fp32.  On
+ * return T = T^K and Q = Q^K (Q^K was chosen against T^{K-1}; T^K is refit to
+ * it).  loss_history_host (optional, 2*iters doubles) receives the objective
+ * after every half step (index 2k: after the S-step of sweep k, 2k+1: after
+ * its T-step); passing it adds one m x n x n product per half step.
+ * opts == NULL means {NONE, 0, QUANTILE_MID, 0, ZERO}.  Synchronises. */
+ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype, int64_t m,
+                                int64_t n, int64_t ldw, const float* H, int64_t ldh,
+                                const float* L, int64_t ldl, int nbits, int iters,
+                                const ganq_options* opts, float* T, uint8_t* Q, int64_t ldq,
+                                double* loss_history_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GANQ_H */

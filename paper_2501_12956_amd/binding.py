@@ -1,0 +1,226 @@
+"""Thin ctypes binding over libganq.so (argument marshalling only).
+
+Every step of the GANQ layer solver runs in the HIP kernels behind the C ABI of
+``include/ganq.h``; torch is used here for device memory and the current
+stream.  There is no fallback: if the library has not been built the import of
+the library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libganq.so")
+
+GANQ_OK, GANQ_ERR_INVALID_ARG, GANQ_ERR_UNSUPPORTED, GANQ_ERR_NOT_PD, GANQ_ERR_WORKSPACE, GANQ_ERR_HIP = range(6)
+GANQ_F16, GANQ_F32 = 0, 1
+PRECOND_NONE, PRECOND_LAMBDA, PRECOND_DIAGDOM, PRECOND_AUTO = range(4)
+INIT_QUANTILE_MID, INIT_QUANTILE_ENDPOINTS, INIT_MINMAX_GRID = range(3)
+EMPTY_ZERO, EMPTY_KEEP = 0, 1
+
+EXPORTS = ["ganq_create", "ganq_destroy", "ganq_workspace_bytes", "ganq_set_workspace",
+           "ganq_status_string", "ganq_last_error", "ganq_build_hessian", "ganq_cholesky",
+           "ganq_init_codebooks", "ganq_update_S", "ganq_update_T", "ganq_layer_loss",
+           "ganq_quantize_layer"]
+
+
+class GanqOptions(ctypes.Structure):
+    _fields_ = [("precond", ctypes.c_int), ("lambda_", ctypes.c_float), ("init", ctypes.c_int),
+                ("init_codebooks", ctypes.c_int), ("empty", ctypes.c_int), ("reserved", ctypes.c_int)]
+
+
+class GanqError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("ganq status %d: %s" % (status, text))
+        self.status = status
+
+
+_lib = None
+
+
+def load_library():
+    """Loads libganq.so; raises if it has not been built (python -m paper_2501_12956_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libganq.so is missing: build it with `python -m paper_2501_12956_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, ci, cf = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+    lib.ganq_create.argtypes = [ctypes.POINTER(vp), ci, vp]
+    lib.ganq_create.restype = ci
+    lib.ganq_destroy.argtypes = [vp]
+    lib.ganq_destroy.restype = ci
+    lib.ganq_workspace_bytes.argtypes = [i64, i64, i64, ci]
+    lib.ganq_workspace_bytes.restype = ctypes.c_size_t
+    lib.ganq_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
+    lib.ganq_set_workspace.restype = ci
+    lib.ganq_status_string.argtypes = [ci]
+    lib.ganq_status_string.restype = ctypes.c_char_p
+    lib.ganq_last_error.argtypes = [vp]
+    lib.ganq_last_error.restype = ctypes.c_char_p
+    lib.ganq_build_hessian.argtypes = [vp, vp, ci, i64, i64, i64, vp, i64, ci]
+    lib.ganq_build_hessian.restype = ci
+    lib.ganq_cholesky.argtypes = [vp, vp, i64, i64, ci, cf, vp, i64, ctypes.POINTER(i64)]
+    lib.ganq_cholesky.restype = ci
+    lib.ganq_init_codebooks.argtypes = [vp, vp, ci, i64, i64, i64, ci, ci, vp]
+    lib.ganq_init_codebooks.restype = ci
+    lib.ganq_update_S.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, ci, vp, i64, vp, i64]
+    lib.ganq_update_S.restype = ci
+    lib.ganq_update_T.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, i64, ci, ci, vp, vp]
+    lib.ganq_update_T.restype = ci
+    lib.ganq_layer_loss.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, vp, i64, ci,
+                                    ctypes.POINTER(ctypes.c_double), vp]
+    lib.ganq_layer_loss.restype = ci
+    lib.ganq_quantize_layer.argtypes = [vp, vp, ci, i64, i64, i64, vp, i64, vp, i64, ci, ci,
+                                        ctypes.POINTER(GanqOptions), vp, vp, i64,
+                                        ctypes.POINTER(ctypes.c_double)]
+    lib.ganq_quantize_layer.restype = ci
+    _lib = lib
+    return lib
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float16:
+        return GANQ_F16
+    if t.dtype == torch.float32:
+        return GANQ_F32
+    raise TypeError("expected a float16 or float32 tensor, got %s" % t.dtype)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _rowmajor(t, name):
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("%s must be a 2-D row-major tensor" % name)
+    return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+class Context:
+    """One ganq_ctx bound to a device, to torch's current stream at creation and to a
+    torch-owned workspace that grows on demand."""
+
+    def __init__(self, device=0, stream=None):
+        self.lib = load_library()
+        self.device = torch.device("cuda", device) if isinstance(device, int) else torch.device(device)
+        dev_index = self.device.index or 0
+        if stream is None and torch.cuda.is_available():
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+        handle = ctypes.c_void_p()
+        st = self.lib.ganq_create(ctypes.byref(handle), dev_index, ctypes.c_void_p(stream or 0))
+        if st != GANQ_OK:
+            raise GanqError(st, self.lib.ganq_status_string(st).decode())
+        self.handle = handle
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.lib.ganq_destroy(self.handle)
+            self.handle = None
+            self._ws = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st):
+        if st != GANQ_OK:
+            raise GanqError(st, self.lib.ganq_last_error(self.handle).decode() or
+                            self.lib.ganq_status_string(st).decode())
+
+    def reserve(self, m, n, p=0, nbits=4):
+        need = self.lib.ganq_workspace_bytes(m, n, p, nbits)
+        if need == 0:
+            raise ValueError("invalid shape for workspace query")
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = None
+            self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
+            self._check(self.lib.ganq_set_workspace(self.handle, _ptr(self._ws), need))
+        return need
+
+    # ---- the seven calls -------------------------------------------------
+    def build_hessian(self, X, H=None, accumulate=False):
+        n, p = X.shape
+        ldx = _rowmajor(X, "X")
+        if H is None:
+            H = torch.empty(n, n, dtype=torch.float32, device=X.device)
+        self.reserve(0, n, p, 4)
+        self._check(self.lib.ganq_build_hessian(self.handle, _ptr(X), _dtype_code(X), n, p, ldx,
+                                                _ptr(H), _rowmajor(H, "H"), int(accumulate)))
+        return H
+
+    def cholesky(self, H, precond=PRECOND_NONE, lam=0.0, L=None, raise_on_fail=True):
+        n = H.shape[0]
+        if L is None:
+            L = torch.empty(n, n, dtype=torch.float32, device=H.device)
+        self.reserve(0, n, 0, 4)
+        info = ctypes.c_int64(0)
+        st = self.lib.ganq_cholesky(self.handle, _ptr(H), n, _rowmajor(H, "H"), precond, lam,
+                                    _ptr(L), _rowmajor(L, "L"), ctypes.byref(info))
+        if st == GANQ_ERR_NOT_PD and not raise_on_fail:
+            return L, info.value
+        self._check(st)
+        return L, info.value
+
+    def init_codebooks(self, W, nbits, init=INIT_QUANTILE_MID, T=None):
+        m, n = W.shape
+        if T is None:
+            T = torch.empty(m, 1 << nbits, dtype=torch.float32, device=W.device)
+        self._check(self.lib.ganq_init_codebooks(self.handle, _ptr(W), _dtype_code(W), m, n,
+                                                 _rowmajor(W, "W"), nbits, init, _ptr(T)))
+        return T
+
+    def update_S(self, W, L, T, nbits, Q=None, want_E=False):
+        m, n = W.shape
+        if Q is None:
+            Q = torch.empty(m, n, dtype=torch.uint8, device=W.device)
+        E = torch.empty(m, n, dtype=torch.float32, device=W.device) if want_E else None
+        self.reserve(m, n, 0, nbits)
+        self._check(self.lib.ganq_update_S(self.handle, _ptr(W), m, n, _rowmajor(W, "W"), _ptr(L),
+                                           _rowmajor(L, "L"), _ptr(T), nbits, _ptr(Q),
+                                           _rowmajor(Q, "Q"), _ptr(E), n if want_E else 0))
+        return (Q, E) if want_E else Q
+
+    def update_T(self, W, H, Q, T, nbits, empty=EMPTY_ZERO, want_counts=False):
+        m, n = W.shape
+        cnt = torch.zeros(m, dtype=torch.int32, device=W.device) if want_counts else None
+        self.reserve(m, n, 0, nbits)
+        self._check(self.lib.ganq_update_T(self.handle, _ptr(W), m, n, _rowmajor(W, "W"), _ptr(H),
+                                           _rowmajor(H, "H"), _ptr(Q), _rowmajor(Q, "Q"), nbits,
+                                           empty, _ptr(T), _ptr(cnt)))
+        return (T, cnt) if want_counts else T
+
+    def layer_loss(self, W, H, T, Q, nbits, want_rows=False):
+        m, n = W.shape
+        rows = torch.empty(m, dtype=torch.float32, device=W.device) if want_rows else None
+        self.reserve(m, n, 0, nbits)
+        out = ctypes.c_double(0.0)
+        self._check(self.lib.ganq_layer_loss(self.handle, _ptr(W), m, n, _rowmajor(W, "W"), _ptr(H),
+                                             _rowmajor(H, "H"), _ptr(T), _ptr(Q), _rowmajor(Q, "Q"),
+                                             nbits, ctypes.byref(out), _ptr(rows)))
+        return (out.value, rows) if want_rows else out.value
+
+    def quantize_layer(self, W, H, nbits, iters, T=None, L=None, precond=PRECOND_NONE, lam=0.0,
+                       init=INIT_QUANTILE_MID, empty=EMPTY_ZERO, Q=None, history=False):
+        m, n = W.shape
+        opts = GanqOptions(precond, lam, init, 1 if T is None else 0, empty, 0)
+        if T is None:
+            T = torch.empty(m, 1 << nbits, dtype=torch.float32, device=W.device)
+        if Q is None:
+            Q = torch.empty(m, n, dtype=torch.uint8, device=W.device)
+        hist = (ctypes.c_double * (2 * iters))() if history and iters > 0 else None
+        self.reserve(m, n, 0, nbits)
+        self._check(self.lib.ganq_quantize_layer(
+            self.handle, _ptr(W), _dtype_code(W), m, n, _rowmajor(W, "W"), _ptr(H),
+            _rowmajor(H, "H"), _ptr(L), _rowmajor(L, "L") if L is not None else 0, nbits, iters,
+            ctypes.byref(opts), _ptr(T), _ptr(Q), _rowmajor(Q, "Q"), hist))
+        if history:
+            return T, Q, list(hist) if hist is not None else []
+        return T, Q

@@ -1,0 +1,383 @@
+// Host side of the C ABI declared in ganq.h: argument checks, workspace
+// carving, and the order in which the gfx950 kernels are enqueued.  No
+// arithmetic of the method lives here.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "ganq_internal.h"
+
+using namespace ganq;
+
+namespace {
+
+ganq_status fail(ganq_ctx* ctx, ganq_status st, const char* msg) {
+  if (ctx != nullptr) ctx->last_error = msg;
+  return st;
+}
+
+ganq_status hip_fail(ganq_ctx* ctx, hipError_t e, const char* where) {
+  if (ctx != nullptr) {
+    ctx->last_error = std::string(where) + ": " + hipGetErrorString(e);
+  }
+  return GANQ_ERR_HIP;
+}
+
+#define GANQ_HIP(ctx, expr)                                     \
+  do {                                                          \
+    hipError_t _e = (expr);                                     \
+    if (_e != hipSuccess) return hip_fail((ctx), _e, #expr);    \
+  } while (0)
+
+#define GANQ_REQUIRE(ctx, cond, msg)                                      \
+  do {                                                                    \
+    if (!(cond)) return fail((ctx), GANQ_ERR_INVALID_ARG, (msg));         \
+  } while (0)
+
+bool nbits_ok(int nbits) { return nbits >= 1 && nbits <= 4; }
+bool dtype_ok(int d) { return d == GANQ_F16 || d == GANQ_F32; }
+
+ganq_status bind_device(ganq_ctx* ctx) {
+  GANQ_HIP(ctx, hipSetDevice(ctx->device));
+  ctx->device_ready = true;
+  return GANQ_OK;
+}
+
+size_t quantize_scratch_bytes(int64_t m, int64_t n, int nbits) {
+  size_t b = 0;
+  b += align_up((size_t)m * n * sizeof(float));        // W in fp32
+  b += align_up((size_t)n * n * sizeof(float));        // L
+  b += align_up((size_t)m * n * sizeof(float));        // G = W H
+  b += cholesky_scratch_bytes(n);
+  b += update_s_scratch_bytes(m, n);
+  b += update_t_scratch_bytes(m, n, nbits);
+  b += loss_scratch_bytes(m, n);
+  return b + 8 * kAlign;
+}
+
+// row losses -> host double; scratch = [E][F][row values][double]
+ganq_status run_loss(ganq_ctx* ctx, Arena& ar, const float* W, int64_t m, int64_t n, int64_t ldw,
+                     const float* H, int64_t ldh, const float* T, const uint8_t* Q, int64_t ldq,
+                     int nbits, double* loss_host, float* row_loss_out) {
+  float* E = (float*)ar.take((size_t)m * n * sizeof(float));
+  float* F = (float*)ar.take((size_t)m * n * sizeof(float));
+  float* rows = (float*)ar.take((size_t)m * sizeof(float));
+  double* total = (double*)ar.take(sizeof(double));
+  if (E == nullptr || F == nullptr || rows == nullptr || total == nullptr)
+    return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the loss evaluation");
+  hipStream_t s = ctx->stream;
+  GANQ_HIP(ctx, launch_residual(s, W, m, n, ldw, T, Q, ldq, nbits, E, n));
+  GANQ_HIP(ctx, launch_gemm_f32(s, 0, 0, m, n, n, 1.f, E, n, H, ldh, 0.f, F, n));
+  float* rl = (row_loss_out != nullptr) ? row_loss_out : rows;
+  GANQ_HIP(ctx, launch_rowdot(s, F, n, E, n, m, n, rl));
+  GANQ_HIP(ctx, launch_sum_f64(s, rl, m, total));
+  GANQ_HIP(ctx, hipMemcpyAsync(loss_host, total, sizeof(double), hipMemcpyDeviceToHost, s));
+  GANQ_HIP(ctx, hipStreamSynchronize(s));
+  return GANQ_OK;
+}
+
+ganq_status run_cholesky(ganq_ctx* ctx, Arena& ar, const float* H, int64_t n, int64_t ldh,
+                         int precond, float lambda, float* L, int64_t ldl, int64_t* info_host) {
+  int* info_dev = (int*)ar.take(cholesky_scratch_bytes(n));
+  if (info_dev == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for Cholesky");
+  hipStream_t s = ctx->stream;
+  int first = (precond == GANQ_PRECOND_AUTO) ? GANQ_PRECOND_NONE : precond;
+  int info = 0;
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    const int mode = (attempt == 0) ? first : GANQ_PRECOND_DIAGDOM;
+    GANQ_HIP(ctx, launch_cholesky(s, H, n, ldh, mode, lambda, L, ldl, info_dev));
+    GANQ_HIP(ctx, hipMemcpyAsync(&info, info_dev, sizeof(int), hipMemcpyDeviceToHost, s));
+    GANQ_HIP(ctx, hipStreamSynchronize(s));
+    if (info == 0 || precond != GANQ_PRECOND_AUTO) break;
+  }
+  if (info_host != nullptr) *info_host = info;
+  if (info != 0) {
+    char buf[96];
+    snprintf(buf, sizeof buf, "matrix not positive definite at pivot %d", info);
+    return fail(ctx, GANQ_ERR_NOT_PD, buf);
+  }
+  return GANQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ganq_status ganq_create(ganq_ctx** out, int device, void* hip_stream) {
+  if (out == nullptr) return GANQ_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (device < 0) return GANQ_ERR_INVALID_ARG;
+  ganq_ctx* c = new (std::nothrow) ganq_ctx();
+  if (c == nullptr) return GANQ_ERR_HIP;
+  c->device = device;
+  c->stream = (hipStream_t)hip_stream;
+  *out = c;
+  return GANQ_OK;
+}
+
+ganq_status ganq_destroy(ganq_ctx* ctx) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  delete ctx;
+  return GANQ_OK;
+}
+
+size_t ganq_workspace_bytes(int64_t m, int64_t n, int64_t p_tokens, int nbits) {
+  if (m < 0 || n <= 0 || p_tokens < 0 || !nbits_ok(nbits)) return 0;
+  size_t q = quantize_scratch_bytes(m, n, nbits);
+  size_t h = hessian_scratch_bytes(n, p_tokens > 0 ? p_tokens : 1) + kAlign;
+  size_t h32 = align_up((size_t)n * n * sizeof(float)) + kAlign;
+  if (h32 > h) h = h32;
+  return q > h ? q : h;
+}
+
+ganq_status ganq_set_workspace(ganq_ctx* ctx, void* dev_ptr, size_t bytes) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  GANQ_REQUIRE(ctx, (dev_ptr != nullptr) == (bytes != 0), "workspace pointer and size disagree");
+  GANQ_REQUIRE(ctx, ((uintptr_t)dev_ptr) % kAlign == 0, "workspace must be 256-byte aligned");
+  ctx->ws = dev_ptr;
+  ctx->ws_bytes = bytes;
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
+const char* ganq_status_string(ganq_status s) {
+  switch (s) {
+    case GANQ_OK: return "ok";
+    case GANQ_ERR_INVALID_ARG: return "invalid argument";
+    case GANQ_ERR_UNSUPPORTED: return "unsupported";
+    case GANQ_ERR_NOT_PD: return "matrix not positive definite";
+    case GANQ_ERR_WORKSPACE: return "workspace missing or too small";
+    case GANQ_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+const char* ganq_last_error(const ganq_ctx* ctx) {
+  return ctx == nullptr ? "" : ctx->last_error.c_str();
+}
+
+ganq_status ganq_build_hessian(ganq_ctx* ctx, const void* X, ganq_dtype x_dtype, int64_t n,
+                               int64_t p, int64_t ldx, float* H, int64_t ldh, int accumulate) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  GANQ_REQUIRE(ctx, dtype_ok(x_dtype), "x_dtype");
+  GANQ_REQUIRE(ctx, n > 0 && p >= 0, "n must be positive and p non-negative");
+  GANQ_REQUIRE(ctx, H != nullptr && ldh >= n, "H / ldh");
+  GANQ_REQUIRE(ctx, p == 0 || (X != nullptr && ldx >= p), "X / ldx");
+  if (x_dtype == GANQ_F16 && p > 0) {
+    if (ldx % 8 != 0 || ((uintptr_t)X) % 16 != 0)
+      return fail(ctx, GANQ_ERR_UNSUPPORTED, "fp16 X needs ldx % 8 == 0 and a 16-byte aligned pointer");
+  }
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  hipStream_t s = ctx->stream;
+  Arena ar(ctx->ws, ctx->ws_bytes);
+  if (x_dtype == GANQ_F16) {
+    float* part = (float*)ar.take(hessian_scratch_bytes(n, p > 0 ? p : 1));
+    if (part == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for H = X X^T");
+    GANQ_HIP(ctx, launch_hessian_f16(s, (const _Float16*)X, n, p, ldx, H, ldh, accumulate, part));
+  } else {
+    float* tmp = (float*)ar.take((size_t)n * n * sizeof(float));
+    if (tmp == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for H = X X^T");
+    GANQ_HIP(ctx, launch_gemm_f32(s, 1, 1, n, n, p, 1.f, (const float*)X, ldx, (const float*)X, ldx,
+                                  0.f, tmp, n));
+    GANQ_HIP(ctx, launch_mirror_lower(s, H, n, ldh, tmp, n, accumulate));
+  }
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
+ganq_status ganq_cholesky(ganq_ctx* ctx, const float* H, int64_t n, int64_t ldh,
+                          ganq_precond precond, float lambda, float* L, int64_t ldl,
+                          int64_t* info_host) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  if (info_host != nullptr) *info_host = 0;
+  GANQ_REQUIRE(ctx, n > 0, "n must be positive");
+  GANQ_REQUIRE(ctx, H != nullptr && ldh >= n, "H / ldh");
+  GANQ_REQUIRE(ctx, L != nullptr && ldl >= n, "L / ldl");
+  GANQ_REQUIRE(ctx, (const void*)H != (const void*)L, "L may not alias H");
+  GANQ_REQUIRE(ctx, precond >= GANQ_PRECOND_NONE && precond <= GANQ_PRECOND_AUTO, "precond");
+  GANQ_REQUIRE(ctx, precond != GANQ_PRECOND_LAMBDA || (lambda > 0.f && std::isfinite(lambda)),
+               "lambda must be positive and finite");
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  Arena ar(ctx->ws, ctx->ws_bytes);
+  st = run_cholesky(ctx, ar, H, n, ldh, precond, lambda, L, ldl, info_host);
+  if (st == GANQ_OK) ctx->last_error.clear();
+  return st;
+}
+
+ganq_status ganq_init_codebooks(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype, int64_t m,
+                                int64_t n, int64_t ldw, int nbits, ganq_init init, float* T) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  GANQ_REQUIRE(ctx, dtype_ok(w_dtype), "w_dtype");
+  GANQ_REQUIRE(ctx, m >= 0 && n > 0, "m, n");
+  GANQ_REQUIRE(ctx, nbits_ok(nbits), "nbits must be in [1, 4]");
+  GANQ_REQUIRE(ctx, init >= GANQ_INIT_QUANTILE_MID && init <= GANQ_INIT_MINMAX_GRID, "init");
+  GANQ_REQUIRE(ctx, m == 0 || (W != nullptr && T != nullptr && ldw >= n), "W / T / ldw");
+  if (n > 32768) return fail(ctx, GANQ_ERR_UNSUPPORTED, "init_codebooks supports n <= 32768");
+  if (m == 0) return GANQ_OK;
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  GANQ_HIP(ctx, launch_init_codebooks(ctx->stream, W, w_dtype == GANQ_F16, m, n, ldw, nbits,
+                                      (int)init, T));
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
+ganq_status ganq_update_S(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                          const float* L, int64_t ldl, const float* T, int nbits, uint8_t* Q,
+                          int64_t ldq, float* E, int64_t lde) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  GANQ_REQUIRE(ctx, m >= 0 && n > 0, "m, n");
+  GANQ_REQUIRE(ctx, nbits_ok(nbits), "nbits must be in [1, 4]");
+  GANQ_REQUIRE(ctx, L != nullptr && ldl >= n, "L / ldl");
+  GANQ_REQUIRE(ctx, m == 0 || (W != nullptr && T != nullptr && Q != nullptr), "W / T / Q");
+  GANQ_REQUIRE(ctx, ldw >= n && ldq >= n, "ldw / ldq");
+  GANQ_REQUIRE(ctx, E == nullptr || lde >= n, "lde");
+  if (m == 0) return GANQ_OK;
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  Arena ar(ctx->ws, ctx->ws_bytes);
+  void* scratch = ar.take(update_s_scratch_bytes(m, n));
+  if (scratch == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the S-update");
+  GANQ_HIP(ctx, launch_update_S(ctx->stream, W, m, n, ldw, L, ldl, T, nbits, Q, ldq, E, lde, scratch));
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
+ganq_status ganq_update_T(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                          const float* H, int64_t ldh, const uint8_t* Q, int64_t ldq, int nbits,
+                          ganq_empty empty, float* T, int32_t* empty_count) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  GANQ_REQUIRE(ctx, m >= 0 && n > 0, "m, n");
+  GANQ_REQUIRE(ctx, nbits_ok(nbits), "nbits must be in [1, 4]");
+  GANQ_REQUIRE(ctx, H != nullptr && ldh >= n, "H / ldh");
+  GANQ_REQUIRE(ctx, m == 0 || (W != nullptr && T != nullptr && Q != nullptr), "W / T / Q");
+  GANQ_REQUIRE(ctx, ldw >= n && ldq >= n, "ldw / ldq");
+  GANQ_REQUIRE(ctx, empty == GANQ_EMPTY_ZERO || empty == GANQ_EMPTY_KEEP, "empty");
+  if (m == 0) return GANQ_OK;
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  Arena ar(ctx->ws, ctx->ws_bytes);
+  float* G = (float*)ar.take((size_t)m * n * sizeof(float));
+  void* scratch = ar.take(update_t_scratch_bytes(m, n, nbits));
+  if (G == nullptr || scratch == nullptr)
+    return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the T-update");
+  hipStream_t s = ctx->stream;
+  GANQ_HIP(ctx, launch_gemm_f32(s, 0, 0, m, n, n, 1.f, W, ldw, H, ldh, 0.f, G, n));
+  GANQ_HIP(ctx, launch_update_T(s, G, n, m, n, H, ldh, Q, ldq, nbits, (int)empty, T, empty_count,
+                                scratch));
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
+ganq_status ganq_layer_loss(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                            const float* H, int64_t ldh, const float* T, const uint8_t* Q,
+                            int64_t ldq, int nbits, double* loss_host, float* row_loss) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  GANQ_REQUIRE(ctx, m >= 0 && n > 0, "m, n");
+  GANQ_REQUIRE(ctx, nbits_ok(nbits), "nbits must be in [1, 4]");
+  GANQ_REQUIRE(ctx, loss_host != nullptr, "loss_host");
+  GANQ_REQUIRE(ctx, H != nullptr && ldh >= n, "H / ldh");
+  GANQ_REQUIRE(ctx, m == 0 || (W != nullptr && T != nullptr && Q != nullptr), "W / T / Q");
+  GANQ_REQUIRE(ctx, ldw >= n && ldq >= n, "ldw / ldq");
+  *loss_host = 0.0;
+  if (m == 0) return GANQ_OK;
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  Arena ar(ctx->ws, ctx->ws_bytes);
+  st = run_loss(ctx, ar, W, m, n, ldw, H, ldh, T, Q, ldq, nbits, loss_host, row_loss);
+  if (st == GANQ_OK) ctx->last_error.clear();
+  return st;
+}
+
+ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype, int64_t m,
+                                int64_t n, int64_t ldw, const float* H, int64_t ldh,
+                                const float* L, int64_t ldl, int nbits, int iters,
+                                const ganq_options* opts, float* T, uint8_t* Q, int64_t ldq,
+                                double* loss_history_host) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  ganq_options o;
+  o.precond = GANQ_PRECOND_NONE;
+  o.lambda = 0.f;
+  o.init = GANQ_INIT_QUANTILE_MID;
+  o.init_codebooks = 0;
+  o.empty = GANQ_EMPTY_ZERO;
+  o.reserved = 0;
+  if (opts != nullptr) o = *opts;
+  GANQ_REQUIRE(ctx, dtype_ok(w_dtype), "w_dtype");
+  GANQ_REQUIRE(ctx, m >= 0 && n > 0, "m, n");
+  GANQ_REQUIRE(ctx, nbits_ok(nbits), "nbits must be in [1, 4]");
+  GANQ_REQUIRE(ctx, iters >= 0, "iters");
+  GANQ_REQUIRE(ctx, H != nullptr && ldh >= n, "H / ldh");
+  GANQ_REQUIRE(ctx, L == nullptr || ldl >= n, "ldl");
+  GANQ_REQUIRE(ctx, m == 0 || (W != nullptr && T != nullptr && Q != nullptr), "W / T / Q");
+  GANQ_REQUIRE(ctx, ldw >= n && ldq >= n, "ldw / ldq");
+  GANQ_REQUIRE(ctx, o.reserved == 0, "options.reserved must be 0");
+  GANQ_REQUIRE(ctx, o.precond >= GANQ_PRECOND_NONE && o.precond <= GANQ_PRECOND_AUTO, "options.precond");
+  GANQ_REQUIRE(ctx, o.precond != GANQ_PRECOND_LAMBDA || (o.lambda > 0.f && std::isfinite(o.lambda)),
+               "options.lambda must be positive and finite");
+  GANQ_REQUIRE(ctx, o.init >= GANQ_INIT_QUANTILE_MID && o.init <= GANQ_INIT_MINMAX_GRID, "options.init");
+  GANQ_REQUIRE(ctx, o.empty == GANQ_EMPTY_ZERO || o.empty == GANQ_EMPTY_KEEP, "options.empty");
+  if (o.init_codebooks && n > 32768)
+    return fail(ctx, GANQ_ERR_UNSUPPORTED, "init_codebooks supports n <= 32768");
+  if (m == 0) return GANQ_OK;
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  hipStream_t s = ctx->stream;
+  Arena ar(ctx->ws, ctx->ws_bytes);
+
+  const float* Wf = nullptr;
+  int64_t ldwf = ldw;
+  if (w_dtype == GANQ_F16) {
+    float* buf = (float*)ar.take((size_t)m * n * sizeof(float));
+    if (buf == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small (W)");
+    GANQ_HIP(ctx, launch_convert_f16_f32(s, (const _Float16*)W, m, n, ldw, buf, n));
+    Wf = buf;
+    ldwf = n;
+  } else {
+    Wf = (const float*)W;
+  }
+  if (L == nullptr) {
+    float* Lbuf = (float*)ar.take((size_t)n * n * sizeof(float));
+    if (Lbuf == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small (L)");
+    int64_t info = 0;
+    Arena sub((char*)ctx->ws + align_up(ar.off), ctx->ws_bytes - align_up(ar.off));
+    st = run_cholesky(ctx, sub, H, n, ldh, o.precond, o.lambda, Lbuf, n, &info);
+    if (st != GANQ_OK) return st;
+    L = Lbuf;
+    ldl = n;
+  }
+  if (o.init_codebooks) {
+    GANQ_HIP(ctx, launch_init_codebooks(s, Wf, 0, m, n, ldwf, nbits, (int)o.init, T));
+  }
+  float* G = (float*)ar.take((size_t)m * n * sizeof(float));
+  void* s_scratch = ar.take(update_s_scratch_bytes(m, n));
+  void* t_scratch = ar.take(update_t_scratch_bytes(m, n, nbits));
+  if (G == nullptr || s_scratch == nullptr || t_scratch == nullptr)
+    return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small (solver scratch)");
+  if (iters > 0) GANQ_HIP(ctx, launch_gemm_f32(s, 0, 0, m, n, n, 1.f, Wf, ldwf, H, ldh, 0.f, G, n));
+
+  for (int k = 0; k < iters; ++k) {
+    GANQ_HIP(ctx, launch_update_S(s, Wf, m, n, ldwf, L, ldl, T, nbits, Q, ldq, nullptr, 0, s_scratch));
+    if (loss_history_host != nullptr) {
+      Arena sub((char*)ctx->ws + align_up(ar.off), ctx->ws_bytes - align_up(ar.off));
+      st = run_loss(ctx, sub, Wf, m, n, ldwf, H, ldh, T, Q, ldq, nbits, &loss_history_host[2 * k], nullptr);
+      if (st != GANQ_OK) return st;
+    }
+    // the fp16 split of H is made on the first sweep and reused afterwards
+    GANQ_HIP(ctx, launch_update_T(s, G, n, m, n, (k == 0) ? H : nullptr, ldh, Q, ldq, nbits,
+                                  (int)o.empty, T, nullptr, t_scratch));
+    if (loss_history_host != nullptr) {
+      Arena sub((char*)ctx->ws + align_up(ar.off), ctx->ws_bytes - align_up(ar.off));
+      st = run_loss(ctx, sub, Wf, m, n, ldwf, H, ldh, T, Q, ldq, nbits, &loss_history_host[2 * k + 1], nullptr);
+      if (st != GANQ_OK) return st;
+    }
+  }
+  GANQ_HIP(ctx, hipStreamSynchronize(s));
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
+}  // extern "C"

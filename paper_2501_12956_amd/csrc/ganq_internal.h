@@ -1,0 +1,101 @@
+// Internal declarations shared by the host-side C ABI and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <string>
+
+#include "ganq.h"
+
+struct ganq_ctx {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  void* ws = nullptr;
+  size_t ws_bytes = 0;
+  bool device_ready = false;
+  std::string last_error;
+};
+
+namespace ganq {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+
+constexpr int64_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + (kAlign - 1)) & ~(size_t)(kAlign - 1); }
+__host__ __device__ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Bump allocator over the caller's workspace.
+struct Arena {
+  char* base;
+  size_t cap;
+  size_t off = 0;
+  Arena(void* p, size_t bytes) : base((char*)p), cap(bytes) {}
+  void* take(size_t bytes) {
+    size_t a = align_up(off);
+    if (base == nullptr || a + bytes > cap) return nullptr;
+    off = a + bytes;
+    return base + a;
+  }
+};
+
+// ---- sizes of scratch regions (shared by ganq_workspace_bytes and the calls) ----
+constexpr int kSlabRows = 16;       // rows per workgroup in the S-update
+constexpr int kHessTile = 128;      // output tile edge of the fp16 H = X X^T kernel
+constexpr int kHessMaxSplit = 16;   // upper bound on token-axis splits
+
+inline int64_t pad_rows(int64_t m) { return ceil_div(m, kSlabRows) * kSlabRows; }
+int hessian_split(int64_t n, int64_t p);
+size_t hessian_scratch_bytes(int64_t n, int64_t p);
+size_t update_s_scratch_bytes(int64_t m, int64_t n);
+size_t update_t_scratch_bytes(int64_t m, int64_t n, int nbits);
+size_t loss_scratch_bytes(int64_t m, int64_t n);
+size_t cholesky_scratch_bytes(int64_t n);
+
+// ---- kernel launchers (all enqueue on `s`, return the HIP error of the launch) ----
+
+// C = alpha * A * op(B) + beta * C, fp32 on the matrix cores.  A is M x K
+// (lda), op(B) is K x N: transb == 0 -> B is K x N (ldb), transb != 0 -> B is
+// N x K (ldb).  lower_only != 0 leaves every element above the diagonal of C
+// untouched and skips the tiles that hold only such elements (M == N expected).
+hipError_t launch_gemm_f32(hipStream_t s, int transb, int lower_only, int64_t M, int64_t N,
+                           int64_t K, float alpha, const float* A, int64_t lda, const float* B,
+                           int64_t ldb, float beta, float* C, int64_t ldc);
+
+hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64_t p, int64_t ldx,
+                              float* H, int64_t ldh, int accumulate, float* partials);
+hipError_t launch_mirror_lower(hipStream_t s, float* H, int64_t n, int64_t ldh, const float* src,
+                               int64_t lds, int accumulate);
+
+hipError_t launch_cholesky(hipStream_t s, const float* H, int64_t n, int64_t ldh, int precond,
+                           float lambda, float* L, int64_t ldl, int* info_dev);
+
+hipError_t launch_init_codebooks(hipStream_t s, const void* W, int w_is_f16, int64_t m, int64_t n,
+                                 int64_t ldw, int nbits, int mode, float* T);
+
+hipError_t launch_convert_f16_f32(hipStream_t s, const _Float16* src, int64_t rows, int64_t cols,
+                                  int64_t ld_src, float* dst, int64_t ld_dst);
+
+hipError_t launch_update_S(hipStream_t s, const float* W, int64_t m, int64_t n, int64_t ldw,
+                           const float* L, int64_t ldl, const float* T, int nbits, uint8_t* Q,
+                           int64_t ldq, float* E, int64_t lde, void* scratch);
+
+// G = W * H is an input here (computed once per layer by the caller of this launcher).
+hipError_t launch_update_T(hipStream_t s, const float* G, int64_t ldg, int64_t m, int64_t n,
+                           const float* H, int64_t ldh, const uint8_t* Q, int64_t ldq, int nbits,
+                           int empty_mode, float* T, int32_t* empty_count, void* scratch);
+
+// row_loss[i] = sum_j F_ij * E_ij with E = W - T[Q] written to Ebuf first (launch_residual),
+// F = E * H by launch_gemm_f32, then launch_rowdot.
+hipError_t launch_residual(hipStream_t s, const float* W, int64_t m, int64_t n, int64_t ldw,
+                           const float* T, const uint8_t* Q, int64_t ldq, int nbits, float* E,
+                           int64_t lde);
+hipError_t launch_rowdot(hipStream_t s, const float* F, int64_t ldf, const float* E, int64_t lde,
+                         int64_t m, int64_t n, float* row_loss);
+hipError_t launch_sum_f64(hipStream_t s, const float* v, int64_t m, double* out_dev);
+
+}  // namespace ganq
