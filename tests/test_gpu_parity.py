@@ -4,7 +4,8 @@ inputs), plus the degenerate cases.  Sizes span several tiles and a ragged tail
 while staying small enough for the oracle to finish in seconds.
 
 Tolerances (derived from the arithmetic):
-  H        |dH_jk| <= 2e-6 sqrt(H_jj H_kk)      fp32 accumulation of exact fp16 products
+  H        |dH_jk| <= h_tol(p) sqrt(H_jj H_kk), h_tol = max(2e-6, 5 eps sqrt(p/3)): fp32 running
+           sums of p products (sequential accumulation error, 4.5 sigma over n^2 entries)
   L        |L L^T - H|_F <= 2e-6 |H|_F, |L - L_ref|_F <= 1e-4 |L_ref|_F
   T^0      1 ulp of fp32
   Q        every choice optimal for its float64 teacher-forced target, or a near tie
@@ -41,11 +42,23 @@ def dev(a, dtype=None):
 
 def make_problem(m, n, p, nbits, seed=0, x_dtype=torch.float16, w_kind="student_t"):
     base = synth.CONFIGS["c3"] if w_kind == "student_t" else synth.CONFIGS["c1"]
-    p = (p + 7) // 8 * 8          # fp16 activations need a leading dimension that is a multiple of 8
+    if x_dtype == torch.float16:  # fp16 activations need a leading dimension that is a multiple of 8
+        p = (p + 7) // 8 * 8
     cfg = synth.scaled_config(base, m=m, n=n, p=p, nbits=nbits)
     W = synth.make_weight(cfg, seed).float()
     X = synth.make_activations(cfg, seed).to(x_dtype)
     return W, X
+
+
+def h_tol(p):
+    return max(2e-6, 5.0 * 2.0 ** -24 * np.sqrt(p / 3.0))
+
+
+def check_H(H, Href, p, label=""):
+    d = np.sqrt(np.diag(Href))
+    rel = np.abs(H - Href) / (np.outer(d, d) + 1e-300)
+    print("%s H: max |dH|/sqrt(HjjHkk) = %.2e (tol %.2e)" % (label, rel.max(), h_tol(p)))
+    assert rel.max() <= h_tol(p)
 
 
 def check_S(W64, L64, T64, Q_gpu, label=""):
@@ -67,15 +80,14 @@ def test_hessian_fp16(ctx, n, p):
     Xg = X.cuda()
     H = ctx.build_hessian(Xg).cpu().numpy().astype(np.float64)
     Href = ref.build_hessian(X.numpy())
-    d = np.sqrt(np.diag(Href))
-    assert np.all(np.abs(H - Href) <= 2e-6 * np.outer(d, d) + 1e-30)
+    check_H(H, Href, p, "fp16 n=%d p=%d" % (n, p))
     assert np.array_equal(H, H.T)
     # streaming: two token chunks accumulate to the same matrix
     if p >= 16:
         half = (p // 2) // 8 * 8
         H2 = ctx.build_hessian(Xg[:, :half].contiguous())
         H2 = ctx.build_hessian(Xg[:, half:].contiguous(), H=H2, accumulate=True).cpu().numpy()
-        assert np.all(np.abs(H2 - Href) <= 2e-6 * np.outer(d, d) + 1e-30)
+        check_H(H2, Href, p, "fp16 two chunks")
 
 
 def test_hessian_fp32_and_strided(ctx):
@@ -83,8 +95,7 @@ def test_hessian_fp32_and_strided(ctx):
     Xg = X.cuda()
     H = ctx.build_hessian(Xg).cpu().numpy().astype(np.float64)
     Href = ref.build_hessian(X.numpy())
-    d = np.sqrt(np.diag(Href))
-    assert np.all(np.abs(H - Href) <= 2e-6 * np.outer(d, d))
+    check_H(H, Href, 515, "fp32")
     # a view with a leading dimension larger than p
     big = torch.zeros(200, 600, dtype=torch.float32, device="cuda")
     big[:, :515] = Xg
@@ -247,8 +258,7 @@ def test_quantize_layer_config1(ctx):
     Wg, Xg = W.cuda(), X.cuda()
     H = ctx.build_hessian(Xg)
     Href = ref.build_hessian(X.numpy())
-    d = np.sqrt(np.diag(Href))
-    assert np.all(np.abs(H.cpu().numpy() - Href) <= 2e-6 * np.outer(d, d))
+    check_H(H.cpu().numpy().astype(np.float64), Href, cfg.p, "c1")
     L, info = ctx.cholesky(H)
     assert info == 0
     K = cfg.iters
