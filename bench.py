@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the GANQ per-layer solver on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3]
+
+One "step" is one pass of the whole hot path over one synthetic layer whose
+inputs already sit in HBM: H = X X^T, Cholesky, quantile codebooks, K_iters
+alternations of S-update and T-update (Algorithm 1), and one evaluation of the
+objective.  The headline workload is the LLaMA-7B q_proj-shaped layer at 4 bits
+(4096 x 4096, X 4096 x 262144 fp16, 10 alternations).
+
+Prints ONE JSON line with the seconds per layer, a per-kernel-class breakdown
+measured with HIP events on the library's stream inside the timed region, the
+roofline figure of the dominant kernel, and the float64 CPU oracle timed on a
+bounded sample of the same workload (baseline only).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_F16_TFLOPS = 2500.0
+PEAK_F32_MFMA_TFLOPS = 157.3
+# plain fp32 vector additions: 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2.4 GHz = 78.6e12 adds/s,
+# i.e. half of the 157.3 TFLOP/s vector FMA figure (an add is one flop, an FMA two)
+PEAK_F32_ADD_TOPS = 78.6
+
+
+def kernel_work(cls, m, n, p, nbits, iters):
+    """Algorithmic work of ONE launch of a kernel class: (bound, work, unit, peak)."""
+    if cls == "hessian":
+        return "mfma", float(n) * n * p, "TFLOP/s", PEAK_F16_TFLOPS          # symmetric half of 2 n^2 p
+    if cls == "cholesky":
+        return "mfma", float(n) ** 3 / 3.0, "TFLOP/s", PEAK_F32_MFMA_TFLOPS
+    if cls == "gemm_wh":
+        return "mfma", 2.0 * m * n * n, "TFLOP/s", PEAK_F32_MFMA_TFLOPS
+    if cls == "update_s":
+        return "mfma", float(m) * n * n, "TFLOP/s", PEAK_F32_MFMA_TFLOPS      # triangular: m n^2 / 2 MACs
+    if cls == "t_accum":
+        return "alu", 0.5 * m * n * n, "TFLOP/s", PEAK_F32_ADD_TOPS           # m n^2 / 2 additions
+    if cls == "loss":
+        return "mfma", 2.0 * m * n * n, "TFLOP/s", PEAK_F32_MFMA_TFLOPS
+    if cls == "t_prep":
+        return "hbm", 4.0 * n * n / 2 + 4.0 * n * n / 2, "GB/s", PEAK_HBM_GBS  # read tril(H), write 2 fp16 halves
+    if cls == "t_pad":
+        return "hbm", 2.0 * m * n, "GB/s", PEAK_HBM_GBS
+    if cls == "t_solve":
+        return "hbm", 5.0 * m * n, "GB/s", PEAK_HBM_GBS                        # G (4 B) + Q (1 B) per element
+    if cls == "init":
+        return "hbm", 6.0 * m * n, "GB/s", PEAK_HBM_GBS
+    return "hbm", 0.0, "GB/s", PEAK_HBM_GBS
+
+
+def cpu_baseline(cfg, X_dev, W_dev, rows=48, tokens=8192):
+    """The float64 oracle timed on the host cores on a bounded sample: H from `tokens`
+    tokens, a full Cholesky, and the K alternations on `rows` rows of W; seconds are then
+    scaled to the whole layer (rows are independent; H is a sum over tokens)."""
+    import numpy as np
+    from oracle import ganq_ref as ref
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    Xs = X_dev[:, :tokens].cpu().numpy()
+    Ws = W_dev[:rows].float().cpu().numpy().astype(np.float64)
+    t0 = time.perf_counter()
+    H = ref.build_hessian(Xs)
+    t_h = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    L, _ = ref.cholesky(H)
+    t_c = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    T0 = ref.init_codebooks(Ws, cfg.nbits)
+    T, Q = ref.quantize_layer(Ws, H, T0, cfg.nbits, cfg.iters, L=L)
+    loss = ref.layer_loss(Ws, H, T, Q)[0]
+    t_s = time.perf_counter() - t0
+    full = t_h * (cfg.p / tokens) + t_c + t_s * (cfg.m / rows)
+    return {
+        "value": full, "unit": "s/layer", "cores": int(threads), "kind": "oracle",
+        "sample": "measured %.1f s: H from %d of %d tokens (%.2f s), full Cholesky (%.2f s), "
+                  "%d alternations + loss on %d of %d rows (%.2f s); scaled linearly to the layer"
+                  % (t_h + t_c + t_s, tokens, cfg.p, t_h, t_c, cfg.iters, rows, cfg.m, t_s),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="c3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the solver has no multi-GPU path); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2501_12956_amd import binding, synth
+
+    cfg = synth.CONFIGS[args.config]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    W = synth.make_weight(cfg, 0, dev)
+    X = synth.make_activations(cfg, 0, dev)
+    Wf = W.float()                      # the objective is evaluated on the fp32 upcast
+    m, n, p = cfg.m, cfg.n, cfg.p
+    ctx = binding.Context(0)
+    ctx.reserve(m, n, p, cfg.nbits)
+    H = torch.empty(n, n, dtype=torch.float32, device=dev)
+    L = torch.empty(n, n, dtype=torch.float32, device=dev)
+    Q = torch.empty(m, n, dtype=torch.uint8, device=dev)
+    state = {}
+
+    def step():
+        ctx.build_hessian(X, H=H)
+        ctx.cholesky(H, L=L)
+        T, _ = ctx.quantize_layer(W, H, cfg.nbits, cfg.iters, L=L, Q=Q)     # T^0 built inside
+        state["loss"] = ctx.layer_loss(Wf, H, T, Q, cfg.nbits)
+        state["T"] = T
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    kernels = {}
+    for cls, (ms, cnt) in prof.items():
+        if cnt == 0:
+            continue
+        bound, work, unit, peak = kernel_work(cls, m, n, p, cfg.nbits, cfg.iters)
+        avg_ms = ms / cnt
+        rate = work / (avg_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9) if avg_ms > 0 else 0.0
+        kernels[cls] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps,
+                        "avg_ms": avg_ms, "bound": bound, "achieved": rate, "peak": peak, "unit": unit,
+                        "frac": rate / peak}
+    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    kd = kernels[dominant]
+    roofline = {"kernel": dominant, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
+                "unit": kd["unit"], "frac": kd["frac"], "traffic": None,
+                "avg_launch_ms": kd["avg_ms"]}
+
+    out = {
+        "metric": "sec per 4096x4096 layer (4-bit, 10 iters) on 1 GPU; % MFMA/HBM roofline",
+        "value": ms_per_step / 1e3, "unit": "s/layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: W %dx%d %s, X %dx%d %s, N=%d bits, %d alternations; step = H build + "
+                               "Cholesky + codebook init + alternations + loss"
+                               % (cfg.name, m, n, str(cfg.w_dtype).replace("torch.", ""), n, p,
+                                  str(cfg.x_dtype).replace("torch.", ""), cfg.nbits, cfg.iters)},
+        "final_loss": state["loss"],
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, X, W)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

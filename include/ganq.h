@@ -163,6 +163,31 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
                                 const ganq_options* opts, float* T, uint8_t* Q, int64_t ldq,
                                 double* loss_history_host);
 
+/* ---- optional per-kernel timing (measurement aid, not part of the method) ------ */
+
+/* Kernel classes the library launches; one step of Algorithm 1 touches all of them. */
+typedef enum {
+  GANQ_K_HESSIAN = 0,  /* H = X X^T product (+ partial-sum reduction) */
+  GANQ_K_CHOLESKY = 1, /* whole blocked factorisation */
+  GANQ_K_INIT = 2,     /* T^0 (and fp16 -> fp32 conversion of W) */
+  GANQ_K_GEMM_WH = 3,  /* G = W H, once per layer */
+  GANQ_K_UPDATE_S = 4, /* one S-update sweep (one launch) */
+  GANQ_K_T_PREP = 5,   /* fp16 split of H, once per layer */
+  GANQ_K_T_PAD = 6,    /* padded copy of Q, once per sweep */
+  GANQ_K_T_ACCUM = 7,  /* one-hot GEMM of the T-update, once per sweep */
+  GANQ_K_T_SOLVE = 8,  /* per-row assembly and solve, once per sweep */
+  GANQ_K_LOSS = 9,     /* objective evaluation */
+  GANQ_K_COUNT = 10
+} ganq_kernel_class;
+
+/* on != 0: bracket every kernel class launched through this context with HIP
+ * events on the context's stream and accumulate the elapsed time; resets the
+ * accumulated figures.  on == 0: stop. */
+ganq_status ganq_profile_enable(ganq_ctx* ctx, int on);
+/* Synchronises the stream, then writes the accumulated milliseconds and number
+ * of bracketed launches per class (arrays of GANQ_K_COUNT, host memory). */
+ganq_status ganq_profile_read(ganq_ctx* ctx, double* ms_host, int64_t* launches_host);
+
 #ifdef __cplusplus
 }
 #endif

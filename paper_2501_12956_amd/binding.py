@@ -24,7 +24,10 @@ EMPTY_ZERO, EMPTY_KEEP = 0, 1
 EXPORTS = ["ganq_create", "ganq_destroy", "ganq_workspace_bytes", "ganq_set_workspace",
            "ganq_status_string", "ganq_last_error", "ganq_build_hessian", "ganq_cholesky",
            "ganq_init_codebooks", "ganq_update_S", "ganq_update_T", "ganq_layer_loss",
-           "ganq_quantize_layer"]
+           "ganq_quantize_layer", "ganq_profile_enable", "ganq_profile_read"]
+
+KERNEL_CLASSES = ["hessian", "cholesky", "init", "gemm_wh", "update_s", "t_prep", "t_pad", "t_accum",
+                  "t_solve", "loss"]
 
 
 class GanqOptions(ctypes.Structure):
@@ -79,6 +82,10 @@ def load_library():
                                         ctypes.POINTER(GanqOptions), vp, vp, i64,
                                         ctypes.POINTER(ctypes.c_double)]
     lib.ganq_quantize_layer.restype = ci
+    lib.ganq_profile_enable.argtypes = [vp, ci]
+    lib.ganq_profile_enable.restype = ci
+    lib.ganq_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    lib.ganq_profile_read.restype = ci
     _lib = lib
     return lib
 
@@ -144,6 +151,18 @@ class Context:
             self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
             self._check(self.lib.ganq_set_workspace(self.handle, _ptr(self._ws), need))
         return need
+
+    # ---- per-kernel-class timing ----------------------------------------
+    def profile_enable(self, on=True):
+        self._check(self.lib.ganq_profile_enable(self.handle, int(on)))
+
+    def profile_read(self):
+        """{class name: (milliseconds, launches)} accumulated since profile_enable(True)."""
+        k = len(KERNEL_CLASSES)
+        ms = (ctypes.c_double * k)()
+        cnt = (ctypes.c_int64 * k)()
+        self._check(self.lib.ganq_profile_read(self.handle, ms, cnt))
+        return {name: (ms[i], cnt[i]) for i, name in enumerate(KERNEL_CLASSES)}
 
     # ---- the seven calls -------------------------------------------------
     def build_hessian(self, X, H=None, accumulate=False):

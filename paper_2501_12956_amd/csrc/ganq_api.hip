@@ -35,6 +35,47 @@ ganq_status hip_fail(ganq_ctx* ctx, hipError_t e, const char* where) {
     if (!(cond)) return fail((ctx), GANQ_ERR_INVALID_ARG, (msg));         \
   } while (0)
 
+// ---- per-class event brackets ----
+struct ProfScope {
+  ganq_ctx* ctx;
+  int cls;
+  hipEvent_t a = nullptr, b = nullptr;
+  bool live = false;
+  static hipEvent_t get(ganq_ctx* c) {
+    if (!c->prof_free.empty()) {
+      hipEvent_t e = c->prof_free.back();
+      c->prof_free.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+  ProfScope(ganq_ctx* c, int k) : ctx(c), cls(k) {
+    if (!c->prof_on) return;
+    a = get(c);
+    b = get(c);
+    if (a == nullptr || b == nullptr) return;
+    live = hipEventRecord(a, c->stream) == hipSuccess;
+  }
+  ~ProfScope() {
+    if (!live) return;
+    if (hipEventRecord(b, ctx->stream) == hipSuccess)
+      ctx->prof_pending.push_back({cls, a, b});
+    ctx->prof_launches[cls] += 1;
+  }
+};
+
+void prof_drain(ganq_ctx* ctx) {
+  for (auto& r : ctx->prof_pending) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) ctx->prof_ms[r.cls] += ms;
+    ctx->prof_free.push_back(r.a);
+    ctx->prof_free.push_back(r.b);
+  }
+  ctx->prof_pending.clear();
+}
+
 bool nbits_ok(int nbits) { return nbits >= 1 && nbits <= 4; }
 bool dtype_ok(int d) { return d == GANQ_F16 || d == GANQ_F32; }
 
@@ -67,6 +108,7 @@ ganq_status run_loss(ganq_ctx* ctx, Arena& ar, const float* W, int64_t m, int64_
   if (E == nullptr || F == nullptr || rows == nullptr || total == nullptr)
     return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the loss evaluation");
   hipStream_t s = ctx->stream;
+  ProfScope prof(ctx, GANQ_K_LOSS);
   GANQ_HIP(ctx, launch_residual(s, W, m, n, ldw, T, Q, ldq, nbits, E, n));
   GANQ_HIP(ctx, launch_gemm_f32(s, 0, 0, m, n, n, 1.f, E, n, H, ldh, 0.f, F, n));
   float* rl = (row_loss_out != nullptr) ? row_loss_out : rows;
@@ -86,7 +128,10 @@ ganq_status run_cholesky(ganq_ctx* ctx, Arena& ar, const float* H, int64_t n, in
   int info = 0;
   for (int attempt = 0; attempt < 2; ++attempt) {
     const int mode = (attempt == 0) ? first : GANQ_PRECOND_DIAGDOM;
-    GANQ_HIP(ctx, launch_cholesky(s, H, n, ldh, mode, lambda, L, ldl, info_dev));
+    {
+      ProfScope prof(ctx, GANQ_K_CHOLESKY);
+      GANQ_HIP(ctx, launch_cholesky(s, H, n, ldh, mode, lambda, L, ldl, info_dev));
+    }
     GANQ_HIP(ctx, hipMemcpyAsync(&info, info_dev, sizeof(int), hipMemcpyDeviceToHost, s));
     GANQ_HIP(ctx, hipStreamSynchronize(s));
     if (info == 0 || precond != GANQ_PRECOND_AUTO) break;
@@ -118,6 +163,11 @@ ganq_status ganq_create(ganq_ctx** out, int device, void* hip_stream) {
 
 ganq_status ganq_destroy(ganq_ctx* ctx) {
   if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  for (auto& r : ctx->prof_pending) {
+    hipEventDestroy(r.a);
+    hipEventDestroy(r.b);
+  }
+  for (auto e : ctx->prof_free) hipEventDestroy(e);
   delete ctx;
   return GANQ_OK;
 }
@@ -138,6 +188,36 @@ ganq_status ganq_set_workspace(ganq_ctx* ctx, void* dev_ptr, size_t bytes) {
   ctx->ws = dev_ptr;
   ctx->ws_bytes = bytes;
   ctx->last_error.clear();
+  return GANQ_OK;
+}
+
+ganq_status ganq_profile_enable(ganq_ctx* ctx, int on) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  if (ctx->device_ready && !ctx->prof_pending.empty()) {
+    GANQ_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    prof_drain(ctx);
+  }
+  ctx->prof_on = on != 0;
+  for (int k = 0; k < GANQ_K_COUNT; ++k) {
+    ctx->prof_ms[k] = 0.0;
+    ctx->prof_launches[k] = 0;
+  }
+  return GANQ_OK;
+}
+
+ganq_status ganq_profile_read(ganq_ctx* ctx, double* ms_host, int64_t* launches_host) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  GANQ_REQUIRE(ctx, ms_host != nullptr && launches_host != nullptr, "output arrays");
+  if (!ctx->prof_pending.empty()) {
+    ganq_status st = bind_device(ctx);
+    if (st != GANQ_OK) return st;
+    GANQ_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    prof_drain(ctx);
+  }
+  for (int k = 0; k < GANQ_K_COUNT; ++k) {
+    ms_host[k] = ctx->prof_ms[k];
+    launches_host[k] = ctx->prof_launches[k];
+  }
   return GANQ_OK;
 }
 
@@ -172,6 +252,7 @@ ganq_status ganq_build_hessian(ganq_ctx* ctx, const void* X, ganq_dtype x_dtype,
   if (st != GANQ_OK) return st;
   hipStream_t s = ctx->stream;
   Arena ar(ctx->ws, ctx->ws_bytes);
+  ProfScope prof(ctx, GANQ_K_HESSIAN);
   if (x_dtype == GANQ_F16) {
     float* part = (float*)ar.take(hessian_scratch_bytes(n, p > 0 ? p : 1));
     if (part == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for H = X X^T");
@@ -219,8 +300,11 @@ ganq_status ganq_init_codebooks(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   if (m == 0) return GANQ_OK;
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
-  GANQ_HIP(ctx, launch_init_codebooks(ctx->stream, W, w_dtype == GANQ_F16, m, n, ldw, nbits,
-                                      (int)init, T));
+  {
+    ProfScope prof(ctx, GANQ_K_INIT);
+    GANQ_HIP(ctx, launch_init_codebooks(ctx->stream, W, w_dtype == GANQ_F16, m, n, ldw, nbits,
+                                        (int)init, T));
+  }
   ctx->last_error.clear();
   return GANQ_OK;
 }
@@ -241,7 +325,10 @@ ganq_status ganq_update_S(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, i
   Arena ar(ctx->ws, ctx->ws_bytes);
   void* scratch = ar.take(update_s_scratch_bytes(m, n));
   if (scratch == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the S-update");
-  GANQ_HIP(ctx, launch_update_S(ctx->stream, W, m, n, ldw, L, ldl, T, nbits, Q, ldq, E, lde, scratch));
+  {
+    ProfScope prof(ctx, GANQ_K_UPDATE_S);
+    GANQ_HIP(ctx, launch_update_S(ctx->stream, W, m, n, ldw, L, ldl, T, nbits, Q, ldq, E, lde, scratch));
+  }
   ctx->last_error.clear();
   return GANQ_OK;
 }
@@ -265,9 +352,26 @@ ganq_status ganq_update_T(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, i
   if (G == nullptr || scratch == nullptr)
     return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the T-update");
   hipStream_t s = ctx->stream;
-  GANQ_HIP(ctx, launch_gemm_f32(s, 0, 0, m, n, n, 1.f, W, ldw, H, ldh, 0.f, G, n));
-  GANQ_HIP(ctx, launch_update_T(s, G, n, m, n, H, ldh, Q, ldq, nbits, (int)empty, T, empty_count,
-                                scratch));
+  {
+    ProfScope prof(ctx, GANQ_K_GEMM_WH);
+    GANQ_HIP(ctx, launch_gemm_f32(s, 0, 0, m, n, n, 1.f, W, ldw, H, ldh, 0.f, G, n));
+  }
+  {
+    ProfScope prof(ctx, GANQ_K_T_PREP);
+    GANQ_HIP(ctx, launch_t_prepare(s, H, m, n, ldh, nbits, scratch));
+  }
+  {
+    ProfScope prof(ctx, GANQ_K_T_PAD);
+    GANQ_HIP(ctx, launch_t_pad(s, Q, m, n, ldq, nbits, scratch));
+  }
+  {
+    ProfScope prof(ctx, GANQ_K_T_ACCUM);
+    GANQ_HIP(ctx, launch_t_accum(s, m, n, nbits, scratch));
+  }
+  {
+    ProfScope prof(ctx, GANQ_K_T_SOLVE);
+    GANQ_HIP(ctx, launch_t_solve(s, G, n, m, n, Q, ldq, nbits, (int)empty, T, empty_count, scratch));
+  }
   ctx->last_error.clear();
   return GANQ_OK;
 }
@@ -333,6 +437,7 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   if (w_dtype == GANQ_F16) {
     float* buf = (float*)ar.take((size_t)m * n * sizeof(float));
     if (buf == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small (W)");
+    ProfScope prof(ctx, GANQ_K_INIT);
     GANQ_HIP(ctx, launch_convert_f16_f32(s, (const _Float16*)W, m, n, ldw, buf, n));
     Wf = buf;
     ldwf = n;
@@ -350,6 +455,7 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
     ldl = n;
   }
   if (o.init_codebooks) {
+    ProfScope prof(ctx, GANQ_K_INIT);
     GANQ_HIP(ctx, launch_init_codebooks(s, Wf, 0, m, n, ldwf, nbits, (int)o.init, T));
   }
   float* G = (float*)ar.take((size_t)m * n * sizeof(float));
@@ -357,18 +463,38 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   void* t_scratch = ar.take(update_t_scratch_bytes(m, n, nbits));
   if (G == nullptr || s_scratch == nullptr || t_scratch == nullptr)
     return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small (solver scratch)");
-  if (iters > 0) GANQ_HIP(ctx, launch_gemm_f32(s, 0, 0, m, n, n, 1.f, Wf, ldwf, H, ldh, 0.f, G, n));
+  if (iters > 0) {
+    {
+      ProfScope prof(ctx, GANQ_K_GEMM_WH);
+      GANQ_HIP(ctx, launch_gemm_f32(s, 0, 0, m, n, n, 1.f, Wf, ldwf, H, ldh, 0.f, G, n));
+    }
+    // the fp16 split of H is made once per layer
+    ProfScope prof(ctx, GANQ_K_T_PREP);
+    GANQ_HIP(ctx, launch_t_prepare(s, H, m, n, ldh, nbits, t_scratch));
+  }
 
   for (int k = 0; k < iters; ++k) {
-    GANQ_HIP(ctx, launch_update_S(s, Wf, m, n, ldwf, L, ldl, T, nbits, Q, ldq, nullptr, 0, s_scratch));
+    {
+      ProfScope prof(ctx, GANQ_K_UPDATE_S);
+      GANQ_HIP(ctx, launch_update_S(s, Wf, m, n, ldwf, L, ldl, T, nbits, Q, ldq, nullptr, 0, s_scratch));
+    }
     if (loss_history_host != nullptr) {
       Arena sub((char*)ctx->ws + align_up(ar.off), ctx->ws_bytes - align_up(ar.off));
       st = run_loss(ctx, sub, Wf, m, n, ldwf, H, ldh, T, Q, ldq, nbits, &loss_history_host[2 * k], nullptr);
       if (st != GANQ_OK) return st;
     }
-    // the fp16 split of H is made on the first sweep and reused afterwards
-    GANQ_HIP(ctx, launch_update_T(s, G, n, m, n, (k == 0) ? H : nullptr, ldh, Q, ldq, nbits,
-                                  (int)o.empty, T, nullptr, t_scratch));
+    {
+      ProfScope prof(ctx, GANQ_K_T_PAD);
+      GANQ_HIP(ctx, launch_t_pad(s, Q, m, n, ldq, nbits, t_scratch));
+    }
+    {
+      ProfScope prof(ctx, GANQ_K_T_ACCUM);
+      GANQ_HIP(ctx, launch_t_accum(s, m, n, nbits, t_scratch));
+    }
+    {
+      ProfScope prof(ctx, GANQ_K_T_SOLVE);
+      GANQ_HIP(ctx, launch_t_solve(s, G, n, m, n, Q, ldq, nbits, (int)o.empty, T, nullptr, t_scratch));
+    }
     if (loss_history_host != nullptr) {
       Arena sub((char*)ctx->ws + align_up(ar.off), ctx->ws_bytes - align_up(ar.off));
       st = run_loss(ctx, sub, Wf, m, n, ldwf, H, ldh, T, Q, ldq, nbits, &loss_history_host[2 * k + 1], nullptr);

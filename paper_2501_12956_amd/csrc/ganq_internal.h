@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include <string>
+#include <vector>
 
 #include "ganq.h"
 
@@ -16,6 +17,13 @@ struct ganq_ctx {
   size_t ws_bytes = 0;
   bool device_ready = false;
   std::string last_error;
+  // optional per-kernel-class timing with HIP events on the context's stream
+  bool prof_on = false;
+  struct ProfRec { int cls; hipEvent_t a, b; };
+  std::vector<ProfRec> prof_pending;
+  std::vector<hipEvent_t> prof_free;
+  double prof_ms[GANQ_K_COUNT] = {0};
+  int64_t prof_launches[GANQ_K_COUNT] = {0};
 };
 
 namespace ganq {
@@ -84,10 +92,17 @@ hipError_t launch_update_S(hipStream_t s, const float* W, int64_t m, int64_t n, 
                            const float* L, int64_t ldl, const float* T, int nbits, uint8_t* Q,
                            int64_t ldq, float* E, int64_t lde, void* scratch);
 
-// G = W * H is an input here (computed once per layer by the caller of this launcher).
-hipError_t launch_update_T(hipStream_t s, const float* G, int64_t ldg, int64_t m, int64_t n,
-                           const float* H, int64_t ldh, const uint8_t* Q, int64_t ldq, int nbits,
-                           int empty_mode, float* T, int32_t* empty_count, void* scratch);
+// T-update in four steps on one scratch region: fp16 split of H (once per layer), padded
+// copy of Q, the one-hot GEMM with fold epilogue, and the per-row assembly + solve
+// (G = W * H is an input, computed once per layer).
+hipError_t launch_t_prepare(hipStream_t s, const float* H, int64_t m, int64_t n, int64_t ldh,
+                            int nbits, void* scratch);
+hipError_t launch_t_pad(hipStream_t s, const uint8_t* Q, int64_t m, int64_t n, int64_t ldq,
+                        int nbits, void* scratch);
+hipError_t launch_t_accum(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch);
+hipError_t launch_t_solve(hipStream_t s, const float* G, int64_t ldg, int64_t m, int64_t n,
+                          const uint8_t* Q, int64_t ldq, int nbits, int empty_mode, float* T,
+                          int32_t* empty_count, void* scratch);
 
 // row_loss[i] = sum_j F_ij * E_ij with E = W - T[Q] written to Ebuf first (launch_residual),
 // F = E * H by launch_gemm_f32, then launch_rowdot.

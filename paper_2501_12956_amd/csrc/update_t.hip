@@ -353,9 +353,11 @@ size_t update_t_scratch_bytes(int64_t m, int64_t n, int nbits) {
   return t_layout(m, n, nbits, nullptr, nullptr);
 }
 
-// Split H once (scratch keeps the result); called by launch_update_T when prep != 0.
-static hipError_t t_prepare(hipStream_t s, const float* H, int64_t n, int64_t ldh,
-                            const TScratch& sc) {
+// fp16 hi/lo split of the strictly lower triangle of H into scratch (once per layer).
+hipError_t launch_t_prepare(hipStream_t s, const float* H, int64_t m, int64_t n, int64_t ldh,
+                            int nbits, void* scratch) {
+  TScratch sc;
+  t_layout(m, n, nbits, (char*)scratch, &sc);
   const int64_t npad = t_npad(n);
   hipLaunchKernelGGL(maxdiag_kernel, dim3(1), dim3(256), 0, s, H, n, ldh, sc.scale, sc.Hdiag);
   hipError_t e = hipGetLastError();
@@ -365,35 +367,48 @@ static hipError_t t_prepare(hipStream_t s, const float* H, int64_t n, int64_t ld
   return hipGetLastError();
 }
 
-hipError_t launch_update_T(hipStream_t s, const float* G, int64_t ldg, int64_t m, int64_t n,
-                           const float* H, int64_t ldh, const uint8_t* Q, int64_t ldq, int nbits,
-                           int empty_mode, float* T, int32_t* empty_count, void* scratch) {
+// zero-padded aligned copy of Q into scratch
+hipError_t launch_t_pad(hipStream_t s, const uint8_t* Q, int64_t m, int64_t n, int64_t ldq,
+                        int nbits, void* scratch) {
+  TScratch sc;
+  t_layout(m, n, nbits, (char*)scratch, &sc);
+  const int64_t npad = t_npad(n), mpad = t_mpad(m, nbits);
+  hipLaunchKernelGGL(pad_q_kernel, dim3((unsigned)ceil_div(npad, 256), (unsigned)mpad), dim3(256), 0,
+                     s, Q, m, n, ldq, npad, sc.Qp);
+  return hipGetLastError();
+}
+
+// partial M_i = sum_{j>k} [Q_ij = a][Q_ik = b] H_jk per group of row tiles (the one-hot GEMM)
+hipError_t launch_t_accum(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch) {
   TScratch sc;
   t_layout(m, n, nbits, (char*)scratch, &sc);
   const int64_t npad = t_npad(n), mpad = t_mpad(m, nbits);
   const int C = 1 << nbits;
-  hipError_t e;
-  if (H != nullptr) {   // H == nullptr: the split from an earlier call on this scratch is reused
-    if ((e = t_prepare(s, H, n, ldh, sc)) != hipSuccess) return e;
-  }
-  hipLaunchKernelGGL(pad_q_kernel, dim3((unsigned)ceil_div(npad, 256), (unsigned)mpad), dim3(256), 0,
-                     s, Q, m, n, ldq, npad, sc.Qp);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
   const int mtiles = (int)(npad / TM);
   const int groups = t_groups(n);
   const size_t shmem = 2 * TM * TLD * 2 + TN * TLD * 2 + 4 * 128 * C * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
-    e = hipFuncSetAttribute((const void*)t_accum_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            2 * TM * TLD * 2 + TN * TLD * 2 + 4 * 128 * 16 * (int)sizeof(float));
+    hipError_t e = hipFuncSetAttribute((const void*)t_accum_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       2 * TM * TLD * 2 + TN * TLD * 2 + 4 * 128 * 16 * (int)sizeof(float));
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   hipLaunchKernelGGL(t_accum_kernel, dim3((unsigned)(mpad / (TN >> nbits)), (unsigned)groups),
                      dim3(256), shmem, s, sc.Hhi, sc.Hlo, npad, sc.Qp, mpad, nbits, mtiles,
                      sc.Apart);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(t_solve_kernel, dim3((unsigned)m), dim3(64), 0, s, sc.Apart, groups, mpad,
+  return hipGetLastError();
+}
+
+// assemble A_i, b_i and solve; G = W H
+hipError_t launch_t_solve(hipStream_t s, const float* G, int64_t ldg, int64_t m, int64_t n,
+                          const uint8_t* Q, int64_t ldq, int nbits, int empty_mode, float* T,
+                          int32_t* empty_count, void* scratch) {
+  TScratch sc;
+  t_layout(m, n, nbits, (char*)scratch, &sc);
+  const int64_t mpad = t_mpad(m, nbits);
+  hipLaunchKernelGGL(t_solve_kernel, dim3((unsigned)m), dim3(64), 0, s, sc.Apart, t_groups(n), mpad,
                      sc.scale, sc.Hdiag, G, ldg, Q, ldq, n, nbits, empty_mode, T, empty_count);
   return hipGetLastError();
 }
