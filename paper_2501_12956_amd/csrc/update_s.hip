@@ -34,6 +34,7 @@ namespace {
 constexpr int SB = 64;          // columns per block
 constexpr int SR = kSlabRows;   // rows per workgroup
 constexpr int PU = 8;           // MFMA groups per software-pipeline stage
+constexpr int NW = 8;           // wavefronts per workgroup (phase 1 splits k over all of them)
 
 template <int CTRL>
 __device__ inline float dpp_f(float v) {
@@ -79,13 +80,27 @@ struct RepLoop {
   }
 };
 
+// Row JL of the staged diagonal block, this lane's 4 columns (only q <= JL / 16 are needed).
 template <int JL>
+__device__ inline void load_lrow(const float (*Ld)[SB + 4], int c, float (&lv)[4]) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) lv[q] = (JL >= 0 && q <= (JL >> 4)) ? Ld[JL < 0 ? 0 : JL][16 * q + c] : 0.f;
+}
+
+template <int JL, bool FULL>
 struct Step {
-  // One column of phase 2 (local column JL of the block).
+  // One column of phase 2 (local column JL of the block).  FULL: the block has all 64
+  // columns, so the 64 steps form one branch-free stretch of code.  The row of L that a
+  // step multiplies by is read from LDS two steps ahead (cur = row JL, nx1 = row JL - 1),
+  // which keeps the LDS latency off the column-to-column dependency chain.
   __device__ static inline void run(int bw, int c, int gshift, float ts, float mid,
                                     const float (&Wr)[4], const float (&rd)[4], float (&acc)[4],
-                                    float (&Er)[4], int (&Ir)[4], const float (*Ld)[SB + 4]) {
-    if (JL < bw) {
+                                    float (&Er)[4], int (&Ir)[4], const float (*Ld)[SB + 4],
+                                    float (&cur)[4], float (&nx1)[4]) {
+    float nx2[4];
+    load_lrow<JL - 2>(Ld, c, nx2);
+    __builtin_amdgcn_sched_barrier(0);
+    if (FULL || JL < bw) {
       constexpr int co = JL & 15, qo = JL >> 4;
       const float tg = row_bcast<co>(fmaf(acc[qo], rd[qo], Wr[qo]));
       const unsigned long long vote = __builtin_amdgcn_ballot_w64(tg > mid);
@@ -97,9 +112,10 @@ struct Step {
         Ir[qo] = idx;
       }
 #pragma unroll
-      for (int q = 0; q <= qo; ++q) acc[q] = fmaf(e, Ld[JL][16 * q + c], acc[q]);
+      for (int q = qo; q >= 0; --q) acc[q] = fmaf(e, cur[q], acc[q]);
     }
-    if constexpr (JL > 0) Step<JL - 1>::run(bw, c, gshift, ts, mid, Wr, rd, acc, Er, Ir, Ld);
+    if constexpr (JL > 0)
+      Step<JL - 1, FULL>::run(bw, c, gshift, ts, mid, Wr, rd, acc, Er, Ir, Ld, nx1, nx2);
   }
 };
 
@@ -114,23 +130,25 @@ struct LFrag {
   float4 b;
 };
 
-__global__ __launch_bounds__(256) void update_S_kernel(const float* __restrict__ W, int64_t m,
+template <bool VECL>
+__global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restrict__ W, int64_t m,
                                                        int64_t n, int64_t ldw,
                                                        const float* __restrict__ L, int64_t ldl,
                                                        const float* __restrict__ rdiag,
                                                        const float* __restrict__ T, int C,
                                                        uint8_t* __restrict__ Q, int64_t ldq,
                                                        float* __restrict__ E, int64_t lde,
-                                                       float* __restrict__ Es, int vecL) {
+                                                       float* __restrict__ Es) {
   __shared__ float Ld[SB][SB + 4];        // diagonal block of L (row = later column)
-  __shared__ float red[4][4][4][64];      // [wave][t][v][lane] partial accumulators
+  __shared__ float red[NW][4][4][64];     // [wave][t][v][lane] partial accumulators
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 15, g = lane >> 4;
   const int r = 4 * wave + g;                       // row within the slab (phase 2)
   const int64_t row0 = (int64_t)blockIdx.x * SR;
   const int64_t row = row0 + r;
-  const bool row_ok = row < m;
+  const bool p2 = wave < 4;                         // wavefronts that run phase 2 (4 rows each)
+  const bool row_ok = p2 && row < m;
   float* __restrict__ Eslab = Es + (int64_t)blockIdx.x * n * SR;
 
   // ---- sort this row's codebook (stable), build midpoints and tie representatives ----
@@ -154,12 +172,12 @@ __global__ __launch_bounds__(256) void update_S_kernel(const float* __restrict__
     const int64_t kstart = j0 + SB;
 
     // ---- stage the diagonal block of L and this block's W ----
-    for (int e4 = tid; e4 < SB * SB / 4; e4 += 256) {
+    for (int e4 = tid; e4 < SB * SB / 4; e4 += 64 * NW) {
       const int rr = e4 / (SB / 4), cc = (e4 % (SB / 4)) * 4;
       const int64_t gr = j0 + rr, gc = j0 + cc;
       float v[4] = {0.f, 0.f, 0.f, 0.f};
       if (gr < n && cc < rr) {
-        if (vecL && gc + 3 < n) {
+        if (VECL && gc + 3 < n) {
           const float4 q4 = *reinterpret_cast<const float4*>(L + gr * ldl + gc);
           v[0] = q4.x; v[1] = q4.y; v[2] = q4.z; v[3] = q4.w;
         } else {
@@ -183,55 +201,81 @@ __global__ __launch_bounds__(256) void update_S_kernel(const float* __restrict__
 #pragma unroll
     for (int t = 0; t < 4; ++t) macc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
     if (kstart < n) {
-      const float* __restrict__ Lcol = L + j0 + 4 * c;
-      const float* __restrict__ Ecol = Eslab + c;
-      auto fetch = [&](int64_t k) {
-        LFrag f;
-        f.a = Ecol[k * SR];
-        if (vecL) {
-          f.b = *reinterpret_cast<const float4*>(Lcol + k * ldl);
+      // This wavefront takes the k-quads qd = wv, wv + NW, ...: iteration `it` covers rows
+      // k = kstart + 4 wv + 4 NW it + g (g = lane / 16).  Operands come through buffer loads:
+      // a scalar resource descriptor based at row kstart + 4 wv, a scalar byte offset per
+      // iteration and a fixed 32-bit lane offset, so a load costs no vector ALU work, and
+      // rows k >= n fall outside the descriptor's range and read as zero (which is what
+      // the ragged tail needs).
+      const int wv = __builtin_amdgcn_readfirstlane(wave);
+      const int64_t krow = kstart + 4 * wv;
+      LFrag fa[PU], fb[PU];
+      if (krow < n) {
+        const int64_t lbytes = ((n - 1 - krow) * ldl + n - j0) * (int64_t)sizeof(float);
+        const int64_t ebytes = (n - krow) * SR * (int64_t)sizeof(float);
+        const __amdgpu_buffer_rsrc_t rl = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(L + krow * ldl + j0), 0, (int)lbytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t re = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(Eslab + krow * SR), 0, (int)ebytes, 0x00020000);
+        const uint32_t loff = (uint32_t)((g * ldl + 4 * c) * sizeof(float));
+        const uint32_t eoff = (uint32_t)((g * SR + c) * sizeof(float));
+        const uint32_t lstep = (uint32_t)(4 * NW * ldl * sizeof(float));   // bytes per iteration in L
+        const uint32_t estep = (uint32_t)(4 * NW * SR * sizeof(float));    // bytes per iteration in E
+        auto fetch = [&](uint32_t it) {
+          LFrag f;
+          f.a = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(re, eoff, it * estep, 0));
+          if (VECL) {
+            f.b = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rl, loff, it * lstep, 0));
+          } else {
+            f.b.x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, loff, it * lstep, 0));
+            f.b.y = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, loff + 4, it * lstep, 0));
+            f.b.z = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, loff + 8, it * lstep, 0));
+            f.b.w = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, loff + 12, it * lstep, 0));
+          }
+          return f;
+        };
+        auto mma = [&](const LFrag& f) {
+          macc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.x, macc[0], 0, 0, 0);
+          macc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.y, macc[1], 0, 0, 0);
+          macc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.z, macc[2], 0, 0, 0);
+          macc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.w, macc[3], 0, 0, 0);
+        };
+        // iterations of this wavefront that touch at least one row < n, in chunks of PU
+        const uint32_t niter = (uint32_t)ceil_div(n - krow, 4 * NW);
+        const uint32_t nch = (niter + PU - 1) / PU;
+        // Two register sets of PU fragments: while the matrix cores consume one set, the
+        // loads that refill the other are issued between the MFMA groups (one fragment per
+        // group of 4 MFMAs); the scheduling barriers pin that interleaving.
+#pragma unroll
+        for (int u = 0; u < PU; ++u) fa[u] = fetch(u);
+        bool in_a = true;
+        for (uint32_t ch = 0; ch + 1 < nch; ++ch) {
+          if (in_a) {
+#pragma unroll
+            for (int u = 0; u < PU; ++u) {
+              fb[u] = fetch((ch + 1) * PU + u);
+              __builtin_amdgcn_sched_barrier(0);
+              mma(fa[u]);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          } else {
+#pragma unroll
+            for (int u = 0; u < PU; ++u) {
+              fa[u] = fetch((ch + 1) * PU + u);
+              __builtin_amdgcn_sched_barrier(0);
+              mma(fb[u]);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+          in_a = !in_a;
+        }
+        if (in_a) {
+#pragma unroll
+          for (int u = 0; u < PU; ++u) mma(fa[u]);
         } else {
-          f.b.x = Lcol[k * ldl]; f.b.y = Lcol[k * ldl + 1];
-          f.b.z = Lcol[k * ldl + 2]; f.b.w = Lcol[k * ldl + 3];
+#pragma unroll
+          for (int u = 0; u < PU; ++u) mma(fb[u]);
         }
-        return f;
-      };
-      auto mma = [&](const LFrag& f) {
-        macc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.x, macc[0], 0, 0, 0);
-        macc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.y, macc[1], 0, 0, 0);
-        macc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.z, macc[2], 0, 0, 0);
-        macc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.w, macc[3], 0, 0, 0);
-      };
-      // this wavefront takes the k-quads qd = wave, wave + 4, ...; lane row g adds to k
-      const int64_t nfull = (n - kstart) / 4;                 // quads with all 4 rows < n
-      const int64_t myfull = (nfull > wave) ? (nfull - wave + 3) / 4 : 0;
-      const int64_t kbase = kstart + 4 * wave + g;            // k of iteration 0
-      int64_t it = 0;
-      if (myfull >= PU) {
-        LFrag cur[PU], nxt[PU];
-#pragma unroll
-        for (int u = 0; u < PU; ++u) cur[u] = fetch(kbase + 16 * (it + u));
-        it += PU;
-        for (; it + PU <= myfull; it += PU) {
-#pragma unroll
-          for (int u = 0; u < PU; ++u) nxt[u] = fetch(kbase + 16 * (it + u));
-#pragma unroll
-          for (int u = 0; u < PU; ++u) mma(cur[u]);
-#pragma unroll
-          for (int u = 0; u < PU; ++u) cur[u] = nxt[u];
-        }
-#pragma unroll
-        for (int u = 0; u < PU; ++u) mma(cur[u]);
-      }
-      for (; it < myfull; ++it) mma(fetch(kbase + 16 * it));
-      // ragged last quad (n - kstart not a multiple of 4): one wavefront, rows masked
-      if ((n - kstart) % 4 != 0 && (nfull % 4) == wave) {
-        const int64_t k = kstart + 4 * nfull + g;
-        LFrag f;
-        f.a = 0.f;
-        f.b = float4{0.f, 0.f, 0.f, 0.f};
-        if (k < n) f = fetch(k);
-        mma(f);
       }
     }
 #pragma unroll
@@ -240,29 +284,40 @@ __global__ __launch_bounds__(256) void update_S_kernel(const float* __restrict__
       for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = macc[t][v];
     __syncthreads();
 
-    // MFMA tile t, lane l', register v holds (row 4*(l'/16) + v, local column 4*(l'%16) + t)
-    float acc[4];
+    if (p2) {
+      // MFMA tile t, lane l', register v holds (row 4*(l'/16) + v, local column 4*(l'%16) + t)
+      float acc[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int jl = 16 * q + c;
-      const int sl = 16 * wave + (jl >> 2), t = jl & 3;
-      acc[q] = (red[0][t][g][sl] + red[1][t][g][sl]) + (red[2][t][g][sl] + red[3][t][g][sl]);
-    }
+      for (int q = 0; q < 4; ++q) {
+        const int jl = 16 * q + c;
+        const int sl = 16 * wave + (jl >> 2), t = jl & 3;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sum += red[w][t][g][sl];
+        acc[q] = sum;
+      }
 
-    // ---- phase 2: the block's columns, right to left ----
-    float Er[4] = {0.f, 0.f, 0.f, 0.f};
-    int Ir[4] = {0, 0, 0, 0};
-    Step<SB - 1>::run(bw, c, gshift, ts, mid, Wr, rd, acc, Er, Ir, Ld);
+      // ---- phase 2: the block's columns, right to left ----
+      float Er[4] = {0.f, 0.f, 0.f, 0.f};
+      int Ir[4] = {0, 0, 0, 0};
+      float l0[4], l1[4];
+      load_lrow<SB - 1>(Ld, c, l0);
+      load_lrow<SB - 2>(Ld, c, l1);
+      if (bw == SB)
+        Step<SB - 1, true>::run(bw, c, gshift, ts, mid, Wr, rd, acc, Er, Ir, Ld, l0, l1);
+      else
+        Step<SB - 1, false>::run(bw, c, gshift, ts, mid, Wr, rd, acc, Er, Ir, Ld, l0, l1);
 
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int64_t col = j0 + 16 * q + c;
-      const int qi = __shfl(rep, (lane & 48) | Ir[q], 64);     // sorted position -> original index
-      if (col < n) {
-        Eslab[col * SR + r] = Er[q];
-        if (row_ok) {
-          Q[row * ldq + col] = (uint8_t)qi;
-          if (E != nullptr) E[row * lde + col] = Er[q];
+      for (int q = 0; q < 4; ++q) {
+        const int64_t col = j0 + 16 * q + c;
+        const int qi = __shfl(rep, (lane & 48) | Ir[q], 64);     // sorted position -> original index
+        if (col < n) {
+          Eslab[col * SR + r] = Er[q];
+          if (row_ok) {
+            Q[row * ldq + col] = (uint8_t)qi;
+            if (E != nullptr) E[row * lde + col] = Er[q];
+          }
         }
       }
     }
@@ -285,8 +340,12 @@ hipError_t launch_update_S(hipStream_t s, const float* W, int64_t m, int64_t n, 
   hipLaunchKernelGGL(rdiag_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, L, n, ldl, rdiag);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(update_S_kernel, dim3((unsigned)ceil_div(m, SR)), dim3(256), 0, s, W, m, n,
-                     ldw, L, ldl, rdiag, T, 1 << nbits, Q, ldq, E, lde, Es, vecL);
+  if (vecL)
+    hipLaunchKernelGGL(update_S_kernel<true>, dim3((unsigned)ceil_div(m, SR)), dim3(64 * NW), 0, s, W,
+                       m, n, ldw, L, ldl, rdiag, T, 1 << nbits, Q, ldq, E, lde, Es);
+  else
+    hipLaunchKernelGGL(update_S_kernel<false>, dim3((unsigned)ceil_div(m, SR)), dim3(64 * NW), 0, s, W,
+                       m, n, ldw, L, ldl, rdiag, T, 1 << nbits, Q, ldq, E, lde, Es);
   return hipGetLastError();
 }
 
