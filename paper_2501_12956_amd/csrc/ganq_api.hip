@@ -319,6 +319,8 @@ ganq_status ganq_update_S(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, i
   GANQ_REQUIRE(ctx, m == 0 || (W != nullptr && T != nullptr && Q != nullptr), "W / T / Q");
   GANQ_REQUIRE(ctx, ldw >= n && ldq >= n, "ldw / ldq");
   GANQ_REQUIRE(ctx, E == nullptr || lde >= n, "lde");
+  if ((uint64_t)n * (uint64_t)ldl * sizeof(float) >= (1ull << 32))
+    return fail(ctx, GANQ_ERR_UNSUPPORTED, "update_S addresses L with 32-bit byte offsets: n * ldl * 4 must stay below 4 GiB");
   if (m == 0) return GANQ_OK;
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
@@ -426,6 +428,8 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   GANQ_REQUIRE(ctx, o.empty == GANQ_EMPTY_ZERO || o.empty == GANQ_EMPTY_KEEP, "options.empty");
   if (o.init_codebooks && n > 32768)
     return fail(ctx, GANQ_ERR_UNSUPPORTED, "init_codebooks supports n <= 32768");
+  if ((uint64_t)n * (uint64_t)(L != nullptr ? ldl : n) * sizeof(float) >= (1ull << 32))
+    return fail(ctx, GANQ_ERR_UNSUPPORTED, "the S-update addresses L with 32-bit byte offsets: n * ldl * 4 must stay below 4 GiB");
   if (m == 0) return GANQ_OK;
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;

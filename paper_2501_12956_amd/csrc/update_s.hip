@@ -171,22 +171,25 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
     const int bw = (int)((n - j0 < SB) ? n - j0 : SB);
     const int64_t kstart = j0 + SB;
 
-    // ---- stage the diagonal block of L and this block's W ----
-    for (int e4 = tid; e4 < SB * SB / 4; e4 += 64 * NW) {
+    // ---- fetch the diagonal block of L (written to LDS after phase 1) and this block's W ----
+    constexpr int STG = SB * SB / 4 / (64 * NW);     // float4 units per thread
+    float stg[STG][4];
+#pragma unroll
+    for (int u = 0; u < STG; ++u) {
+      const int e4 = tid + u * 64 * NW;
       const int rr = e4 / (SB / 4), cc = (e4 % (SB / 4)) * 4;
       const int64_t gr = j0 + rr, gc = j0 + cc;
-      float v[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) stg[u][i] = 0.f;
       if (gr < n && cc < rr) {
         if (VECL && gc + 3 < n) {
           const float4 q4 = *reinterpret_cast<const float4*>(L + gr * ldl + gc);
-          v[0] = q4.x; v[1] = q4.y; v[2] = q4.z; v[3] = q4.w;
+          stg[u][0] = q4.x; stg[u][1] = q4.y; stg[u][2] = q4.z; stg[u][3] = q4.w;
         } else {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = (gc + i < n) ? L[gr * ldl + gc + i] : 0.f;
+          for (int i = 0; i < 4; ++i) stg[u][i] = (gc + i < n) ? L[gr * ldl + gc + i] : 0.f;
         }
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) Ld[rr][cc + i] = (cc + i < rr) ? v[i] : 0.f;
     }
     float Wr[4], rd[4];
 #pragma unroll
@@ -282,6 +285,13 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
     for (int t = 0; t < 4; ++t)
 #pragma unroll
       for (int v = 0; v < 4; ++v) red[wave][t][v][lane] = macc[t][v];
+#pragma unroll
+    for (int u = 0; u < STG; ++u) {
+      const int e4 = tid + u * 64 * NW;
+      const int rr = e4 / (SB / 4), cc = (e4 % (SB / 4)) * 4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) Ld[rr][cc + i] = (cc + i < rr) ? stg[u][i] : 0.f;
+    }
     __syncthreads();
 
     if (p2) {
