@@ -88,19 +88,29 @@ __global__ __launch_bounds__(256) void pad_q_kernel(const uint8_t* __restrict__ 
 }
 
 // ---- the GEMM with fold epilogue ----
+// LDS (dynamic): two stages of { A hi tile, A lo tile, one-hot B tile } and the per-wavefront
+// fold accumulators.  The one-hot tile is never rebuilt: it starts as zeros and each thread
+// owns a fixed set of (row i, k) positions whose single 1 it moves - it clears the 1 it
+// wrote when the stage was last used and sets the new one (in-order LDS writes of one
+// thread), so staging B costs a few 16-bit LDS writes instead of a compare per element.
+constexpr int T_STAGE_BYTES = 2 * TM * TLD * 2 + TN * TLD * 2;
+constexpr int T_NSTAGE = 1;   // one LDS stage: two barriers per k-step, two workgroups per CU
+
+template <int NBITS>
 __global__ __launch_bounds__(256) void t_accum_kernel(const _Float16* __restrict__ Hhi,
                                                       const _Float16* __restrict__ Hlo,
                                                       int64_t npad, const uint8_t* __restrict__ Qp,
-                                                      int64_t mpad, int nbits, int mtiles,
+                                                      int64_t mpad, int mtiles,
                                                       float* __restrict__ Apart) {
+  constexpr int C = 1 << NBITS;
+  constexpr int RW = TN >> NBITS;             // rows i per workgroup
+  constexpr int EPT = (RW * TK) / 256;        // (i, k) positions per thread and stage: 32 >> NBITS
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  _Float16 (*AsHi)[TLD] = reinterpret_cast<_Float16 (*)[TLD]>(smem);
-  _Float16 (*AsLo)[TLD] = reinterpret_cast<_Float16 (*)[TLD]>(smem + TM * TLD * 2);
-  _Float16 (*Bs)[TLD] = reinterpret_cast<_Float16 (*)[TLD]>(smem + 2 * TM * TLD * 2);
-  float* Aw = reinterpret_cast<float*>(smem + 2 * TM * TLD * 2 + TN * TLD * 2);  // [4][128*C]
+  auto As_hi = [&](int st) { return reinterpret_cast<_Float16 (*)[TLD]>(smem + st * T_STAGE_BYTES); };
+  auto As_lo = [&](int st) { return reinterpret_cast<_Float16 (*)[TLD]>(smem + st * T_STAGE_BYTES + TM * TLD * 2); };
+  auto Bs_of = [&](int st) { return reinterpret_cast<_Float16 (*)[TLD]>(smem + st * T_STAGE_BYTES + 2 * TM * TLD * 2); };
+  float* Aw = reinterpret_cast<float*>(smem + T_NSTAGE * T_STAGE_BYTES);        // [4][128*C]
 
-  const int C = 1 << nbits;
-  const int RW = TN >> nbits;                 // rows i per workgroup
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
   const int kh = lane >> 5, l32 = lane & 31;
@@ -108,11 +118,19 @@ __global__ __launch_bounds__(256) void t_accum_kernel(const _Float16* __restrict
   const int group = blockIdx.y;
 
   for (int e = tid; e < 4 * 128 * C; e += 256) Aw[e] = 0.f;
+  for (int st = 0; st < T_NSTAGE; ++st) {
+    _Float16* bz = &Bs_of(st)[0][0];
+    for (int e = tid; e < TN * TLD / 8; e += 256) reinterpret_cast<uint4*>(bz)[e] = uint4{0u, 0u, 0u, 0u};
+  }
 
-  // one-hot expansion: this thread owns pair (il, b) and all TK k of a stage
-  const int ex_il = tid >> nbits, ex_b = tid & (C - 1);
-  const uint8_t* __restrict__ qrow = Qp + (i0 + ex_il) * npad;
+  // one-hot staging: this thread owns row il and the EPT consecutive k from kk0 of every stage
+  const int ex_il = (tid * EPT) / TK, ex_kk0 = (tid * EPT) % TK;
+  const uint8_t* __restrict__ qrow = Qp + (i0 + ex_il) * npad + ex_kk0;
+  int old_code[1][EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) old_code[0][e] = -1;
   const int lrow = tid >> 2, lk = (tid & 3) * 8;
+  __syncthreads();
 
   for (int half = 0; half < 2; ++half) {
     const int mt = (half == 0) ? group : mtiles - 1 - group;
@@ -128,44 +146,51 @@ __global__ __launch_bounds__(256) void t_accum_kernel(const _Float16* __restrict
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-    half8 rhi[2], rlo[2];
-    uint4 rq[2];
-    auto fetch = [&](int64_t k0) {
+    // Global operands are fetched two k-steps ahead into two alternating register sets: a
+    // set is written to LDS at the top of its k-step and refilled right away for the k-step
+    // after next, so a load has two MFMA sections to complete.
+    struct Regs {
+      half8 hi[2], lo[2];
+      uint8_t q[EPT];
+    };
+    auto fetch = [&](Regs& r, int64_t k0) {
 #pragma unroll
       for (int ps = 0; ps < 2; ++ps) {
         const int64_t off = (jt0 + lrow + 64 * ps) * npad + k0 + lk;
-        rhi[ps] = *reinterpret_cast<const half8*>(Hhi + off);
-        rlo[ps] = *reinterpret_cast<const half8*>(Hlo + off);
+        r.hi[ps] = *reinterpret_cast<const half8*>(Hhi + off);
+        r.lo[ps] = *reinterpret_cast<const half8*>(Hlo + off);
       }
-      rq[0] = *reinterpret_cast<const uint4*>(qrow + k0);
-      rq[1] = *reinterpret_cast<const uint4*>(qrow + k0 + 16);
+      if constexpr (EPT == 2) {
+        const uint16_t w = *reinterpret_cast<const uint16_t*>(qrow + k0);
+        r.q[0] = (uint8_t)(w & 0xff); r.q[1] = (uint8_t)(w >> 8);
+      } else if constexpr (EPT == 4) {
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(qrow + k0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r.q[e] = (uint8_t)((w >> (8 * e)) & 0xff);
+      } else {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) r.q[e] = qrow[k0 + e];
+      }
     };
-
-    fetch(0);
-    for (int64_t k0 = 0; k0 < kend; k0 += TK) {
-      __syncthreads();
+    _Float16 (*AsHi)[TLD] = As_hi(0);
+    _Float16 (*AsLo)[TLD] = As_lo(0);
+    _Float16 (*Bs)[TLD] = Bs_of(0);
+    auto kstep = [&](Regs& r, int64_t k0) {
+      __syncthreads();                      // every wavefront is done reading the previous stage
 #pragma unroll
       for (int ps = 0; ps < 2; ++ps) {
-        *reinterpret_cast<half8*>(&AsHi[lrow + 64 * ps][lk]) = rhi[ps];
-        *reinterpret_cast<half8*>(&AsLo[lrow + 64 * ps][lk]) = rlo[ps];
+        *reinterpret_cast<half8*>(&AsHi[lrow + 64 * ps][lk]) = r.hi[ps];
+        *reinterpret_cast<half8*>(&AsLo[lrow + 64 * ps][lk]) = r.lo[ps];
       }
 #pragma unroll
-      for (int w4 = 0; w4 < 2; ++w4) {
-        const uint32_t words[4] = {rq[w4].x, rq[w4].y, rq[w4].z, rq[w4].w};
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-          half8 oh;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const uint32_t wd = words[hh * 2 + (e >> 2)];
-            const int code = (wd >> (8 * (e & 3))) & 0xff;
-            oh[e] = (code == ex_b) ? (_Float16)1 : (_Float16)0;
-          }
-          *reinterpret_cast<half8*>(&Bs[tid][w4 * 16 + hh * 8]) = oh;
-        }
+      for (int e = 0; e < EPT; ++e) {
+        const int code = r.q[e] & (C - 1);
+        if (old_code[0][e] >= 0) Bs[ex_il * C + old_code[0][e]][ex_kk0 + e] = (_Float16)0;
+        Bs[ex_il * C + code][ex_kk0 + e] = (_Float16)1;
+        old_code[0][e] = code;
       }
       __syncthreads();
-      if (k0 + TK < kend) fetch(k0 + TK);
+      if (k0 + 2 * TK < kend) fetch(r, k0 + 2 * TK);
 #pragma unroll
       for (int ks = 0; ks < TK; ks += 16) {
         half8 ahi[2], alo[2], bf[4];
@@ -185,24 +210,63 @@ __global__ __launch_bounds__(256) void t_accum_kernel(const _Float16* __restrict
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo[mi], bf[ni], acc[mi][ni], 0, 0, 0);
           }
       }
+    };
+    Regs r0, r1;
+    fetch(r0, 0);
+    if (TK < kend) fetch(r1, TK);
+    for (int64_t k0 = 0; k0 < kend; k0 += 2 * TK) {     // kend is a multiple of 2 TK (TM = 4 TK)
+      kstep(r0, k0);
+      kstep(r1, k0 + TK);
     }
 
-    // fold: Z[j, (il, b)] -> Aw[wave][il_w][Q[i][j]][b]
+    // fold: Z[j, (il, b)] -> Aw[wave][il_w][Q[i][j]][b].  The codes of this lane's 32 rows j
+    // are fetched first (8 dwords per row i), so that the loads overlap instead of each
+    // waiting behind an LDS add.
     float* __restrict__ myA = Aw + wave * 128 * C;
+    uint32_t qd[4][2][4];
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
-      const int colw = ni * 32 + l32;                 // pair index within this wave's 128
-      const int ilw = colw >> nbits, b = colw & (C - 1);
+      const int ilw = (ni * 32 + l32) >> NBITS;
       const uint8_t* __restrict__ qr = Qp + (i0 + wc * (RW >> 1) + ilw) * npad + jt0 + wr * 64;
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int jl = mi * 32 + (v >> 2) * 8 + kh * 4 + (v & 3);
-          const int a = qr[jl] & (C - 1);
-          atomicAdd(&myA[(ilw * C + a) * C + b], acc[mi][ni][v]);
-        }
+        for (int vq = 0; vq < 4; ++vq)
+          qd[ni][mi][vq] = *reinterpret_cast<const uint32_t*>(qr + mi * 32 + vq * 8 + kh * 4);
     }
+    // LDS float atomics are serialised lane by lane on this chip, so the adds are plain
+    // read-modify-writes instead: in each of two passes only the lanes of one half (kh) are
+    // active, which makes every active lane's bin (its own column (il, b), any code a) private
+    // to it; LDS operations of one wavefront execute in program order, so a later step sees
+    // the earlier one's write.  The four column tiles (ni) form independent streams.
+    int base[4];
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+      const int colw = ni * 32 + l32;                 // pair index within this wave's 128
+      base[ni] = (colw >> NBITS) * C * C + (colw & (C - 1));
+    }
+    for (int pass = 0; pass < 2; ++pass) {
+      if (kh == pass) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            // register v of the tile is row mi*32 + (v>>2)*8 + kh*4 + (v&3) of this wave's 64
+            float x[4];
+            int ad[4];
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) {
+              const int a = (qd[ni][mi][v >> 2] >> (8 * (v & 3))) & (C - 1);
+              ad[ni] = base[ni] + a * C;
+              x[ni] = myA[ad[ni]];
+            }
+#pragma unroll
+            for (int ni = 0; ni < 4; ++ni) myA[ad[ni]] = x[ni] + acc[mi][ni][v];
+          }
+      }
+    }
+    // the stage that the next row tile writes first may still be read by slower wavefronts
+    __syncthreads();
   }
   __syncthreads();
   // Apart[group][i][a*C + b] = copy(wr = 0) + copy(wr = 1)
@@ -230,24 +294,34 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
   const int64_t i = blockIdx.x;
   const int tid = threadIdx.x;
 
-  // per-code sums over the row: lane = 4 * code + part, each part strides over j
-  {
-    const int a = tid >> 2, part = tid & 3;
+  // per-code sums over the row: lane l takes columns l, l + 64, ... (coalesced) and adds into
+  // its own column of LDS bins; the 64 partial sums per code are then added in a fixed order
+  __shared__ float binD[16][64], binB[16][64];
+  __shared__ int binC[16][64];
+  for (int a = 0; a < C; ++a) {
+    binD[a][tid] = 0.f;
+    binB[a][tid] = 0.f;
+    binC[a][tid] = 0;
+  }
+  for (int64_t j = tid; j < n; j += 64) {
+    const int a = Q[i * ldq + j] & (C - 1);
+    binD[a][tid] += Hdiag[j];      // lane-private bins: plain read-modify-write
+    binB[a][tid] += G[i * ldg + j];
+    binC[a][tid] += 1;
+  }
+  __syncthreads();
+  if (tid < C) {
     double sd = 0.0, sb = 0.0;
     int c0 = 0;
-    if (a < C) {
-      for (int64_t j = part; j < n; j += 4) {
-        if ((Q[i * ldq + j] & (C - 1)) == a) {
-          sd += (double)Hdiag[j];
-          sb += (double)G[i * ldg + j];
-          ++c0;
-        }
-      }
+    for (int l = 0; l < 64; ++l) {
+      sd += (double)binD[tid][l];
+      sb += (double)binB[tid][l];
+      c0 += binC[tid][l];
     }
-    // combine the 4 parts in a fixed order
-    sd += __shfl_xor(sd, 1, 64); sb += __shfl_xor(sb, 1, 64); c0 += __shfl_xor(c0, 1, 64);
-    sd += __shfl_xor(sd, 2, 64); sb += __shfl_xor(sb, 2, 64); c0 += __shfl_xor(c0, 2, 64);
-    if (part == 0 && a < C) { Dg[a] = sd; rhs[a] = sb; cnt[a] = c0; dead[a] = (c0 == 0); }
+    Dg[tid] = sd;
+    rhs[tid] = sb;
+    cnt[tid] = c0;
+    dead[tid] = (c0 == 0);
   }
   __syncthreads();
   const double inv_s = (double)scale[1];
@@ -379,26 +453,34 @@ hipError_t launch_t_pad(hipStream_t s, const uint8_t* Q, int64_t m, int64_t n, i
 }
 
 // partial M_i = sum_{j>k} [Q_ij = a][Q_ik = b] H_jk per group of row tiles (the one-hot GEMM)
-hipError_t launch_t_accum(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch) {
+template <int NBITS>
+static hipError_t launch_t_accum_n(hipStream_t s, int64_t m, int64_t n, void* scratch) {
   TScratch sc;
-  t_layout(m, n, nbits, (char*)scratch, &sc);
-  const int64_t npad = t_npad(n), mpad = t_mpad(m, nbits);
-  const int C = 1 << nbits;
+  t_layout(m, n, NBITS, (char*)scratch, &sc);
+  const int64_t npad = t_npad(n), mpad = t_mpad(m, NBITS);
+  const int C = 1 << NBITS;
   const int mtiles = (int)(npad / TM);
   const int groups = t_groups(n);
-  const size_t shmem = 2 * TM * TLD * 2 + TN * TLD * 2 + 4 * 128 * C * sizeof(float);
+  const size_t shmem = T_NSTAGE * T_STAGE_BYTES + 4 * 128 * C * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)t_accum_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       2 * TM * TLD * 2 + TN * TLD * 2 + 4 * 128 * 16 * (int)sizeof(float));
+    hipError_t e = hipFuncSetAttribute((const void*)t_accum_kernel<NBITS>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(t_accum_kernel, dim3((unsigned)(mpad / (TN >> nbits)), (unsigned)groups),
-                     dim3(256), shmem, s, sc.Hhi, sc.Hlo, npad, sc.Qp, mpad, nbits, mtiles,
-                     sc.Apart);
+  hipLaunchKernelGGL(t_accum_kernel<NBITS>, dim3((unsigned)(mpad / (TN >> NBITS)), (unsigned)groups),
+                     dim3(256), shmem, s, sc.Hhi, sc.Hlo, npad, sc.Qp, mpad, mtiles, sc.Apart);
   return hipGetLastError();
+}
+
+hipError_t launch_t_accum(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch) {
+  switch (nbits) {
+    case 1: return launch_t_accum_n<1>(s, m, n, scratch);
+    case 2: return launch_t_accum_n<2>(s, m, n, scratch);
+    case 3: return launch_t_accum_n<3>(s, m, n, scratch);
+    default: return launch_t_accum_n<4>(s, m, n, scratch);
+  }
 }
 
 // assemble A_i, b_i and solve; G = W H
