@@ -53,7 +53,7 @@ struct Arena {
 
 // ---- sizes of scratch regions (shared by ganq_workspace_bytes and the calls) ----
 constexpr int kSlabRows = 16;       // rows per workgroup in the S-update
-constexpr int kHessTile = 128;      // output tile edge of the fp16 H = X X^T kernel
+constexpr int kHessTile = 256;      // output tile edge of the fp16 H = X X^T kernel
 constexpr int kHessMaxSplit = 16;   // upper bound on token-axis splits
 
 inline int64_t pad_rows(int64_t m) { return ceil_div(m, kSlabRows) * kSlabRows; }

@@ -2,7 +2,7 @@
 // cores: fp16 x fp16 products, fp32 accumulation (v_mfma_f32_32x32x16_f16).
 //
 // X is n x p row-major, so both operands of the product are k-contiguous.
-// Only the tiles on or below the diagonal are computed (H is symmetric); the
+// Only the 256 x 256 tiles on or below the diagonal are computed (H is symmetric); the
 // token axis is split across workgroups so that small n still fills the chip,
 // each split writes its partial tile to scratch, and a second kernel sums the
 // partials in a fixed order (bit-reproducible, no float atomics) and writes
@@ -12,10 +12,13 @@
 namespace ganq {
 namespace {
 
-constexpr int HT = kHessTile;   // 128 x 128 output tile per workgroup
+constexpr int HT = kHessTile;   // 256 x 256 output tile per workgroup
 constexpr int HK = 32;          // k per LDS stage
 constexpr int HPAD = 8;         // halfs of row padding in LDS
+constexpr int HLD = HK + HPAD;
+constexpr int HSTAGE = 2 * HT * HLD * 2;   // bytes of one stage: A tile + B tile
 
+// Eight consecutive halfs of row `row` from column k, zero outside [0, n) x [., kend).
 __device__ inline half8 load_half8(const _Float16* __restrict__ X, int64_t row, int64_t k,
                                    int64_t n, int64_t kend, int64_t ldx) {
   half8 r;
@@ -28,9 +31,13 @@ __device__ inline half8 load_half8(const _Float16* __restrict__ X, int64_t row, 
   return r;
 }
 
-__global__ __launch_bounds__(256) void hessian_f16_kernel(const _Float16* __restrict__ X, int64_t n,
-                                                          int64_t p, int64_t ldx, int64_t chunk,
-                                                          float* __restrict__ partials) {
+// 4 wavefronts in a 2 x 2 grid, each owning a 128 x 128 sub-tile as 4 x 4 MFMA tiles of
+// 32 x 32 (256 accumulator registers): 16 MFMAs per 8 LDS fragment reads keeps the LDS at
+// half of its bandwidth.  Two LDS stages, one barrier per k-step: while a stage is being
+// multiplied the registers fetched one step earlier are written to the other stage and the
+// loads of the step after that are issued.
+__device__ inline void hessian_tile(const _Float16* __restrict__ X, int64_t n, int64_t p, int64_t ldx,
+                                    int64_t chunk, float* __restrict__ partials) {
   // triangular tile index -> (bm, bn), bn <= bm
   const int t = blockIdx.x;
   int bm = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
@@ -41,68 +48,93 @@ __global__ __launch_bounds__(256) void hessian_f16_kernel(const _Float16* __rest
   const int64_t kbeg = (int64_t)split * chunk;
   const int64_t kend = (kbeg + chunk < p) ? kbeg + chunk : p;
 
-  __shared__ _Float16 As[HT][HK + HPAD];
-  __shared__ _Float16 Bs[HT][HK + HPAD];
+  extern __shared__ __attribute__((aligned(16))) unsigned char hsm[];
+  auto As_of = [&](int st) { return reinterpret_cast<_Float16 (*)[HLD]>(hsm + st * HSTAGE); };
+  auto Bs_of = [&](int st) { return reinterpret_cast<_Float16 (*)[HLD]>(hsm + st * HSTAGE + HT * HLD * 2); };
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
   const int kh = lane >> 5, l32 = lane & 31;
   const int64_t m0 = (int64_t)bm * HT, n0 = (int64_t)bn * HT;
 
-  floatx16 acc[2][2];
+  floatx16 acc[4][4];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int lrow = tid >> 2, lk = (tid & 3) * 8;
-  half8 ra[2], rb[2];
+  half8 ra[4], rb[4];
   auto fetch = [&](int64_t k0) {
 #pragma unroll
-    for (int ps = 0; ps < 2; ++ps) {
+    for (int ps = 0; ps < 4; ++ps) {
       ra[ps] = load_half8(X, m0 + lrow + 64 * ps, k0 + lk, n, kend, ldx);
       rb[ps] = load_half8(X, n0 + lrow + 64 * ps, k0 + lk, n, kend, ldx);
     }
   };
-
-  if (kbeg < kend) fetch(kbeg);
-  for (int64_t k0 = kbeg; k0 < kend; k0 += HK) {
-    __syncthreads();
+  auto stage_regs = [&](int st) {
+    _Float16 (*As)[HLD] = As_of(st);
+    _Float16 (*Bs)[HLD] = Bs_of(st);
 #pragma unroll
-    for (int ps = 0; ps < 2; ++ps) {
+    for (int ps = 0; ps < 4; ++ps) {
       *reinterpret_cast<half8*>(&As[lrow + 64 * ps][lk]) = ra[ps];
       *reinterpret_cast<half8*>(&Bs[lrow + 64 * ps][lk]) = rb[ps];
     }
+  };
+
+  if (kbeg < kend) {
+    fetch(kbeg);
+    stage_regs(0);
+    if (kbeg + HK < kend) fetch(kbeg + HK);
+  }
+  int st = 0;
+#pragma unroll 1
+  for (int64_t k0 = kbeg; k0 < kend; k0 += HK) {
     __syncthreads();
-    if (k0 + HK < kend) fetch(k0 + HK);
+    _Float16 (*As)[HLD] = As_of(st);
+    _Float16 (*Bs)[HLD] = Bs_of(st);
 #pragma unroll
     for (int ks = 0; ks < HK; ks += 16) {
-      half8 a0 = *reinterpret_cast<const half8*>(&As[wr * 64 + l32][ks + 8 * kh]);
-      half8 a1 = *reinterpret_cast<const half8*>(&As[wr * 64 + 32 + l32][ks + 8 * kh]);
-      half8 b0 = *reinterpret_cast<const half8*>(&Bs[wc * 64 + l32][ks + 8 * kh]);
-      half8 b1 = *reinterpret_cast<const half8*>(&Bs[wc * 64 + 32 + l32][ks + 8 * kh]);
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b1, acc[1][1], 0, 0, 0);
+      half8 af[4], bfr[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        af[i] = *reinterpret_cast<const half8*>(&As[wr * 128 + i * 32 + l32][ks + 8 * kh]);
+        bfr[i] = *reinterpret_cast<const half8*>(&Bs[wc * 128 + i * 32 + l32][ks + 8 * kh]);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
+    if (k0 + HK < kend) {
+      stage_regs(st ^ 1);
+      if (k0 + 2 * HK < kend) fetch(k0 + 2 * HK);
+    }
+    st ^= 1;
   }
 
   float* out = partials + (int64_t)split * n * n;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int64_t col = n0 + wc * 64 + j * 32 + l32;
+    for (int j = 0; j < 4; ++j) {
+      const int64_t col = n0 + wc * 128 + j * 32 + l32;
       if (col >= n) continue;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int64_t row = m0 + wr * 64 + i * 32 + (v >> 2) * 8 + kh * 4 + (v & 3);
-        if (row < n) out[row * n + col] = acc[i][j][v];
+        const int64_t row = m0 + wr * 128 + i * 32 + (v >> 2) * 8 + kh * 4 + (v & 3);
+        if (row < n && col <= row) out[row * n + col] = acc[i][j][v];
       }
     }
+}
+
+__global__ __launch_bounds__(256) void hessian_f16_kernel(const _Float16* __restrict__ X, int64_t n,
+                                                          int64_t p, int64_t ldx, int64_t chunk,
+                                                          float* __restrict__ partials) {
+  hessian_tile(X, n, p, ldx, chunk, partials);
 }
 
 // H[i][j] = H[j][i] = (accumulate ? H[i][j] : 0) + sum_s src[s][i][j] for i >= j.
@@ -139,7 +171,7 @@ int hessian_split(int64_t n, int64_t p) {
   const int64_t nt = ceil_div(n, HT);
   const int64_t tiles = nt * (nt + 1) / 2;
   int split = 1;
-  while (split < kHessMaxSplit && tiles * split < 2048 && p / (split * 2) >= 2048) split *= 2;
+  while (split < kHessMaxSplit && tiles * split < 1024 && p / (split * 2) >= 2048) split *= 2;
   return split;
 }
 
@@ -154,7 +186,14 @@ hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64
   int64_t chunk = ceil_div(ceil_div(p, split), HK) * HK;
   const int64_t nt = ceil_div(n, HT);
   dim3 grid((unsigned)(nt * (nt + 1) / 2), (unsigned)split);
-  hipLaunchKernelGGL(hessian_f16_kernel, grid, dim3(256), 0, s, X, n, p, ldx, chunk, partials);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t ea = hipFuncSetAttribute((const void*)hessian_f16_kernel,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 2 * HSTAGE);
+    if (ea != hipSuccess) return ea;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(hessian_f16_kernel, grid, dim3(256), 2 * HSTAGE, s, X, n, p, ldx, chunk, partials);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   dim3 g2((unsigned)ceil_div(n, 32), (unsigned)ceil_div(n, 32));
