@@ -100,8 +100,9 @@ const char* ganq_last_error(const ganq_ctx* ctx);
 /* ---- the seven calls of the hot path ---------------------------------------- */
 
 /* H = X X^T (Algorithm 1; Eq. (9)).  X is n x p (features x tokens) with
- * leading dimension ldx >= p, fp16 or fp32 storage (fp32 input is rounded to
- * fp16 for the matrix-core product; accumulation is fp32).  H is n x n fp32,
+ * leading dimension ldx >= p, fp16 or fp32 storage (fp16 products are exact in
+ * the fp32 accumulator; fp32 input takes fp32 matrix-core products, nothing is
+ * rounded down).  H is n x n fp32,
  * both triangles written.  accumulate != 0 adds to the H already there
  * (streaming token chunks).  Requires p % 8 == 0 and ldx % 8 == 0 for fp16. */
 ganq_status ganq_build_hessian(ganq_ctx* ctx, const void* X, ganq_dtype x_dtype, int64_t n,
