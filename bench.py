@@ -58,7 +58,7 @@ def kernel_work(cls, m, n, p, nbits, iters):
     return "hbm", 0.0, "GB/s", PEAK_HBM_GBS
 
 
-def cpu_baseline(cfg, X_dev, W_dev, rows=48, tokens=8192):
+def cpu_baseline(cfg, X_dev, W_dev, rows=256, tokens=16384):
     """The float64 oracle timed on the host cores on a bounded sample: H from `tokens`
     tokens, a full Cholesky, and the K alternations on `rows` rows of W; seconds are then
     scaled to the whole layer (rows are independent; H is a sum over tokens)."""

@@ -245,8 +245,11 @@ ganq_status ganq_build_hessian(ganq_ctx* ctx, const void* X, ganq_dtype x_dtype,
   GANQ_REQUIRE(ctx, H != nullptr && ldh >= n, "H / ldh");
   GANQ_REQUIRE(ctx, p == 0 || (X != nullptr && ldx >= p), "X / ldx");
   if (x_dtype == GANQ_F16 && p > 0) {
-    if (ldx % 8 != 0 || ((uintptr_t)X) % 16 != 0)
-      return fail(ctx, GANQ_ERR_UNSUPPORTED, "fp16 X needs ldx % 8 == 0 and a 16-byte aligned pointer");
+    if (p % 8 != 0 || ldx % 8 != 0 || ((uintptr_t)X) % 16 != 0)
+      return fail(ctx, GANQ_ERR_UNSUPPORTED,
+                  "fp16 X needs p % 8 == 0, ldx % 8 == 0 and a 16-byte aligned pointer");
+    if (ldx >= ((int64_t)1 << 22))
+      return fail(ctx, GANQ_ERR_UNSUPPORTED, "fp16 X needs ldx < 2^22 (32-bit offsets inside a 256-row block)");
   }
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;

@@ -7,111 +7,146 @@
 // each split writes its partial tile to scratch, and a second kernel sums the
 // partials in a fixed order (bit-reproducible, no float atomics) and writes
 // both triangles of H.
+//
+// Operand tiles go from global memory straight into LDS (buffer_load ... lds): no
+// registers are held across the MFMA block and no LDS store instructions are issued.  Such
+// a load writes 64 x 16 bytes to consecutive LDS addresses, so the LDS tile cannot be
+// padded; instead the 16-byte chunks of a row are stored in an XOR-permuted order
+// (chunk c of row r at position c ^ (r & 7)), which the lanes apply on the global side
+// when they choose what to fetch and on the LDS side when they read MFMA fragments.
 #include "ganq_internal.h"
 
 namespace ganq {
 namespace {
 
 constexpr int HT = kHessTile;   // 256 x 256 output tile per workgroup
-constexpr int HK = 32;          // k per LDS stage
-constexpr int HPAD = 8;         // halfs of row padding in LDS
-constexpr int HLD = HK + HPAD;
-constexpr int HSTAGE = 2 * HT * HLD * 2;   // bytes of one stage: A tile + B tile
+constexpr int HK = 64;          // tokens per LDS stage: one 128-byte line per row
+constexpr int HS = 2;           // LDS stages
+constexpr int HROWB = HK * 2;   // bytes per LDS row
+constexpr int HTILEB = HT * HROWB;
+constexpr int HSTAGEB = 2 * HTILEB;          // A rows + B rows
+constexpr int HNW = 8;          // wavefronts: 2 x 4, each 128 x 64 of the tile
+constexpr int HDPW = (HT / 8) / HNW;         // direct loads per wavefront, operand and stage
 
-// Eight consecutive halfs of row `row` from column k, zero outside [0, n) x [., kend).
-__device__ inline half8 load_half8(const _Float16* __restrict__ X, int64_t row, int64_t k,
-                                   int64_t n, int64_t kend, int64_t ldx) {
-  half8 r;
-  if (row < n && k + 7 < kend) {
-    r = *reinterpret_cast<const half8*>(X + row * ldx + k);
-  } else {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) r[i] = (row < n && k + i < kend) ? X[row * ldx + k + i] : (_Float16)0;
-  }
+typedef int int4v __attribute__((ext_vector_type(4)));
+
+// One wavefront-wide direct load: lane l's 16 bytes land at LDS byte lds_addr + 16 l.
+// The compiler does not see these loads, so its own vmcnt waits can only be too early for
+// them, never for its own loads (the counter retires in order); the kernel waits for them
+// explicitly before the barrier that publishes a stage.
+__device__ inline void load16_to_lds(int4v rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+__device__ inline void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// raw buffer descriptor over [base, base + bytes): loads beyond it return zero
+__device__ inline int4v make_rsrc(const void* base, int64_t bytes) {
+  const uint64_t ad = (uint64_t)(uintptr_t)base;
+  int4v r;
+  r[0] = (int)(uint32_t)ad;
+  r[1] = (int)(uint32_t)((ad >> 32) & 0xffffu);
+  r[2] = (int)(uint32_t)bytes;
+  r[3] = 0x00020000;
   return r;
 }
 
-// 4 wavefronts in a 2 x 2 grid, each owning a 128 x 128 sub-tile as 4 x 4 MFMA tiles of
-// 32 x 32 (256 accumulator registers): 16 MFMAs per 8 LDS fragment reads keeps the LDS at
-// half of its bandwidth.  Two LDS stages, one barrier per k-step: while a stage is being
-// multiplied the registers fetched one step earlier are written to the other stage and the
-// loads of the step after that are issued.
-__device__ inline void hessian_tile(const _Float16* __restrict__ X, int64_t n, int64_t p, int64_t ldx,
-                                    int64_t chunk, float* __restrict__ partials) {
+// 8 wavefronts (2 per SIMD) in a 2 x 4 grid, each owning 128 x 64 of the tile as 4 x 2 MFMA
+// tiles of 32 x 32 (128 accumulator registers).  Two LDS stages of 64 tokens, one barrier
+// per stage: after the barrier the loads of the next stage are issued into the buffer that
+// every wavefront has just finished reading, then the current stage is multiplied.
+__global__ __launch_bounds__(64 * HNW) void hessian_f16_kernel(const _Float16* __restrict__ X, int64_t n,
+                                                              int64_t p, int64_t ldx, int64_t chunk,
+                                                              int ntiles, int nsplit,
+                                                              float* __restrict__ partials) {
+  // Workgroups are dealt to the 8 XCDs round-robin by their flat index.  Work items are
+  // ordered (split, tile) and each XCD takes a contiguous eighth of that list, so that the
+  // workgroups sharing an L2 stream the same token range and neighbouring row blocks of X.
+  const int64_t total = (int64_t)ntiles * nsplit;
+  const int64_t per = (total + 7) / 8;
+  const int64_t q = blockIdx.x >> 3;
+  const int64_t item = (int64_t)(blockIdx.x & 7) * per + q;
+  if (q >= per || item >= total) return;
+  const int split = (int)(item / ntiles);
   // triangular tile index -> (bm, bn), bn <= bm
-  const int t = blockIdx.x;
+  const int t = (int)(item % ntiles);
   int bm = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
   while ((int64_t)(bm + 1) * (bm + 2) / 2 <= t) ++bm;
   while ((int64_t)bm * (bm + 1) / 2 > t) --bm;
   const int bn = t - (int)((int64_t)bm * (bm + 1) / 2);
-  const int split = blockIdx.y;
   const int64_t kbeg = (int64_t)split * chunk;
   const int64_t kend = (kbeg + chunk < p) ? kbeg + chunk : p;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char hsm[];
-  auto As_of = [&](int st) { return reinterpret_cast<_Float16 (*)[HLD]>(hsm + st * HSTAGE); };
-  auto Bs_of = [&](int st) { return reinterpret_cast<_Float16 (*)[HLD]>(hsm + st * HSTAGE + HT * HLD * 2); };
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)hsm;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave >> 1, wc = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wr = wave >> 2, wc = wave & 3;
   const int kh = lane >> 5, l32 = lane & 31;
   const int64_t m0 = (int64_t)bm * HT, n0 = (int64_t)bn * HT;
 
-  floatx16 acc[4][4];
+  // descriptors over the row blocks of the two operands: rows >= n read as zero
+  const int64_t rowsA = (n - m0 < HT) ? n - m0 : HT, rowsB = (n - n0 < HT) ? n - n0 : HT;
+  const int4v rsA = make_rsrc(X + m0 * ldx, ((rowsA - 1) * ldx + p) * 2);
+  const int4v rsB = make_rsrc(X + n0 * ldx, ((rowsB - 1) * ldx + p) * 2);
+
+  // One direct load covers 8 rows x 128 bytes: lane -> row (lane / 8) and LDS chunk position
+  // (lane % 8), which holds chunk position ^ (row & 7) of the row.
+  const int dr = lane >> 3;
+  const int dc = (lane & 7) ^ dr;
+  uint32_t voff[HDPW];
+#pragma unroll
+  for (int j = 0; j < HDPW; ++j)
+    voff[j] = (uint32_t)(((int64_t)((wave + HNW * j) * 8 + dr) * ldx + dc * 8) * 2);
+  const int64_t klane = dc * 8;
+
+  auto issue = [&](int64_t k0, int st) {
+    const bool ok = k0 + klane < kend;     // p % 8 == 0: a chunk is wholly inside or outside
+    const uint32_t soff = (uint32_t)(k0 * 2);
+    const uint32_t sbase = lds0 + st * HSTAGEB;
+#pragma unroll
+    for (int j = 0; j < HDPW; ++j) {
+      const uint32_t vo = ok ? voff[j] : 0x80000000u;   // beyond any descriptor: reads zero
+      load16_to_lds(rsA, sbase + (wave + HNW * j) * 1024, vo, soff);
+      load16_to_lds(rsB, sbase + HTILEB + (wave + HNW * j) * 1024, vo, soff);
+    }
+  };
+
+  floatx16 acc[4][2];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int lrow = tid >> 2, lk = (tid & 3) * 8;
-  half8 ra[4], rb[4];
-  auto fetch = [&](int64_t k0) {
-#pragma unroll
-    for (int ps = 0; ps < 4; ++ps) {
-      ra[ps] = load_half8(X, m0 + lrow + 64 * ps, k0 + lk, n, kend, ldx);
-      rb[ps] = load_half8(X, n0 + lrow + 64 * ps, k0 + lk, n, kend, ldx);
-    }
-  };
-  auto stage_regs = [&](int st) {
-    _Float16 (*As)[HLD] = As_of(st);
-    _Float16 (*Bs)[HLD] = Bs_of(st);
-#pragma unroll
-    for (int ps = 0; ps < 4; ++ps) {
-      *reinterpret_cast<half8*>(&As[lrow + 64 * ps][lk]) = ra[ps];
-      *reinterpret_cast<half8*>(&Bs[lrow + 64 * ps][lk]) = rb[ps];
-    }
-  };
-
-  if (kbeg < kend) {
-    fetch(kbeg);
-    stage_regs(0);
-    if (kbeg + HK < kend) fetch(kbeg + HK);
-  }
+  const int rswz = l32 & 7;
+  const int nk = (int)((kend - kbeg + HK - 1) / HK);
+  if (nk > 0) issue(kbeg, 0);
   int st = 0;
 #pragma unroll 1
-  for (int64_t k0 = kbeg; k0 < kend; k0 += HK) {
+  for (int k = 0; k < nk; ++k) {
+    wait_all_loads();
     __syncthreads();
-    _Float16 (*As)[HLD] = As_of(st);
-    _Float16 (*Bs)[HLD] = Bs_of(st);
+    if (k + 1 < nk) issue(kbeg + (int64_t)(k + 1) * HK, st ^ 1);
+    const unsigned char* As = hsm + st * HSTAGEB;
+    const unsigned char* Bs = As + HTILEB;
 #pragma unroll
-    for (int ks = 0; ks < HK; ks += 16) {
-      half8 af[4], bfr[4];
+    for (int ks = 0; ks < HK / 16; ++ks) {
+      half8 af[4], bfr[2];
+      const int cpos = ((2 * ks + kh) ^ rswz) * 16;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        af[i] = *reinterpret_cast<const half8*>(&As[wr * 128 + i * 32 + l32][ks + 8 * kh]);
-        bfr[i] = *reinterpret_cast<const half8*>(&Bs[wc * 128 + i * 32 + l32][ks + 8 * kh]);
-      }
+      for (int i = 0; i < 4; ++i)
+        af[i] = *reinterpret_cast<const half8*>(As + (wr * 128 + i * 32 + l32) * HROWB + cpos);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        bfr[j] = *reinterpret_cast<const half8*>(Bs + (wc * 64 + j * 32 + l32) * HROWB + cpos);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    if (k0 + HK < kend) {
-      stage_regs(st ^ 1);
-      if (k0 + 2 * HK < kend) fetch(k0 + 2 * HK);
     }
     st ^= 1;
   }
@@ -120,8 +155,8 @@ __device__ inline void hessian_tile(const _Float16* __restrict__ X, int64_t n, i
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int64_t col = n0 + wc * 128 + j * 32 + l32;
+    for (int j = 0; j < 2; ++j) {
+      const int64_t col = n0 + wc * 64 + j * 32 + l32;
       if (col >= n) continue;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -129,12 +164,6 @@ __device__ inline void hessian_tile(const _Float16* __restrict__ X, int64_t n, i
         if (row < n && col <= row) out[row * n + col] = acc[i][j][v];
       }
     }
-}
-
-__global__ __launch_bounds__(256) void hessian_f16_kernel(const _Float16* __restrict__ X, int64_t n,
-                                                          int64_t p, int64_t ldx, int64_t chunk,
-                                                          float* __restrict__ partials) {
-  hessian_tile(X, n, p, ldx, chunk, partials);
 }
 
 // H[i][j] = H[j][i] = (accumulate ? H[i][j] : 0) + sum_s src[s][i][j] for i >= j.
@@ -168,10 +197,11 @@ __global__ __launch_bounds__(256) void reduce_mirror_kernel(float* __restrict__ 
 }  // namespace
 
 int hessian_split(int64_t n, int64_t p) {
+  // about eight workgroups per compute unit, each with at least 2048 tokens
   const int64_t nt = ceil_div(n, HT);
   const int64_t tiles = nt * (nt + 1) / 2;
   int split = 1;
-  while (split < kHessMaxSplit && tiles * split < 1024 && p / (split * 2) >= 2048) split *= 2;
+  while (split < kHessMaxSplit && tiles * split < 2048 && p / (split * 2) >= 2048) split *= 2;
   return split;
 }
 
@@ -180,20 +210,23 @@ size_t hessian_scratch_bytes(int64_t n, int64_t p) {
   return align_up((size_t)hessian_split(n, p) * (size_t)n * (size_t)n * sizeof(float));
 }
 
+// Requires p % 8 == 0, ldx % 8 == 0, ldx < 2^22 and a 16-byte aligned X (checked by the caller).
 hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64_t p, int64_t ldx,
                               float* H, int64_t ldh, int accumulate, float* partials) {
   const int split = hessian_split(n, p);
   int64_t chunk = ceil_div(ceil_div(p, split), HK) * HK;
   const int64_t nt = ceil_div(n, HT);
-  dim3 grid((unsigned)(nt * (nt + 1) / 2), (unsigned)split);
+  const int ntiles = (int)(nt * (nt + 1) / 2);
+  dim3 grid((unsigned)(8 * ceil_div((int64_t)ntiles * split, 8)));
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t ea = hipFuncSetAttribute((const void*)hessian_f16_kernel,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 2 * HSTAGE);
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, HS * HSTAGEB);
     if (ea != hipSuccess) return ea;
     attr_set = true;
   }
-  hipLaunchKernelGGL(hessian_f16_kernel, grid, dim3(256), 2 * HSTAGE, s, X, n, p, ldx, chunk, partials);
+  hipLaunchKernelGGL(hessian_f16_kernel, grid, dim3(64 * HNW), HS * HSTAGEB, s, X, n, p, ldx, chunk,
+                     ntiles, split, partials);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   dim3 g2((unsigned)ceil_div(n, 32), (unsigned)ceil_div(n, 32));
