@@ -15,21 +15,20 @@
 // v_mfma_f32_32x32x16_f16.  Only k < j is visited (H is symmetric):
 //   M_i[a, b] = sum_j [Q_ij == a] Z[j, (i,b)],   A_i = M_i + M_i^T + Diag(D_i),
 //   D_i[a] = sum_{j: Q_ij == a} H_jj.
-// The fold over j is done in the GEMM epilogue with LDS adds into per-wavefront
-// copies (fixed order, no global float atomics); partial M_i per group of row
-// tiles of H go to scratch and are summed in float64 by the solve kernel, which
-// also forms D_i and b_i, drops unused codes (pseudo-inverse reading: their
-// entry is 0, or kept) and solves the reduced system by Cholesky in float64.
+// The fold over j runs on the matrix cores as well, straight from the accumulator
+// registers (see t_accum_kernel); partial M_i per group of row tiles of H go to
+// scratch and are summed in float64 by the solve kernel, which also forms D_i and
+// b_i, drops unused codes (pseudo-inverse reading: their entry is 0, or kept) and
+// solves the reduced system by Cholesky in float64.
 #include "ganq_internal.h"
 
 namespace ganq {
 namespace {
 
 constexpr int TM = 128;    // rows j of H per tile
-constexpr int TN = 256;    // (row i, code b) pairs per workgroup
+constexpr int TN = 512;    // (row i, code b) pairs per workgroup
 constexpr int TK = 32;     // k per stage
-constexpr int TPAD = 8;    // halfs of LDS row padding
-constexpr int TLD = TK + TPAD;
+constexpr int TNW = 8;     // wavefronts per workgroup, each 128 x 64 of the tile
 
 // ---- per-layer preparation: fp16 hi/lo split of the strictly lower triangle of H ----
 __global__ __launch_bounds__(256) void maxdiag_kernel(const float* __restrict__ H, int64_t n,
@@ -57,11 +56,12 @@ __global__ __launch_bounds__(256) void maxdiag_kernel(const float* __restrict__ 
   }
 }
 
+// Hs[j][k / 32][piece][k % 32]: the hi and lo pieces of 32 consecutive k share one 128-byte
+// line, which is what one row of an LDS stage holds.
 __global__ __launch_bounds__(256) void split_lower_kernel(const float* __restrict__ H, int64_t n,
                                                           int64_t ldh, int64_t npad,
                                                           const float* __restrict__ scale,
-                                                          _Float16* __restrict__ Hhi,
-                                                          _Float16* __restrict__ Hlo) {
+                                                          _Float16* __restrict__ Hs) {
   const int64_t j = blockIdx.y;                                   // row of H
   const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;      // column
   if (k >= npad) return;
@@ -73,8 +73,9 @@ __global__ __launch_bounds__(256) void split_lower_kernel(const float* __restric
     hi = (_Float16)v;
     lo = (_Float16)(v - (float)hi);
   }
-  Hhi[j * npad + k] = hi;
-  Hlo[j * npad + k] = lo;
+  const int64_t o = j * 2 * npad + (k >> 5) * 64 + (k & 31);
+  Hs[o] = hi;
+  Hs[o + 32] = lo;
 }
 
 // zero-padded, 16-byte aligned copy of Q
@@ -88,194 +89,232 @@ __global__ __launch_bounds__(256) void pad_q_kernel(const uint8_t* __restrict__ 
 }
 
 // ---- the GEMM with fold epilogue ----
-// LDS (dynamic): two stages of { A hi tile, A lo tile, one-hot B tile } and the per-wavefront
-// fold accumulators.  The one-hot tile is never rebuilt: it starts as zeros and each thread
-// owns a fixed set of (row i, k) positions whose single 1 it moves - it clears the 1 it
-// wrote when the stage was last used and sets the new one (in-order LDS writes of one
-// thread), so staging B costs a few 16-bit LDS writes instead of a compare per element.
-constexpr int T_STAGE_BYTES = 2 * TM * TLD * 2 + TN * TLD * 2;
-constexpr int T_NSTAGE = 1;   // one LDS stage: two barriers per k-step, two workgroups per CU
+// LDS: T_S stages of { A tile: TM rows x 128 bytes (hi | lo of 32 k), one-hot B tile: TN rows
+// x 64 bytes }.  A tiles arrive by direct-to-LDS buffer loads; such a load writes 64 x 16
+// consecutive bytes, so rows cannot be padded and the 16-byte chunks of a row are stored in
+// XOR-permuted order instead (A: chunk c of row r at c ^ (r & 7); B: c ^ ((r >> 1) & 3)).
+// The one-hot tile is never rebuilt: it starts as zeros and each thread owns a fixed set of
+// (row i, k) positions whose single 1 it moves - it clears the 1 it wrote when the stage
+// was last used and sets the new one (in-order LDS writes of one thread).
+constexpr int T_S = 2;
+constexpr int T_AROWB = 128;
+constexpr int T_ATILEB = TM * T_AROWB;
+constexpr int T_BROWB = TK * 2;
+constexpr int T_BTILEB = TN * T_BROWB;
+constexpr int T_STAGEB = T_ATILEB + T_BTILEB;
 
+typedef int int4v __attribute__((ext_vector_type(4)));
+
+// One wavefront-wide direct load: lane l's 16 bytes land at LDS byte lds_addr + 16 l.  The
+// compiler does not see these loads; the kernel waits for them (vmcnt) before the barrier
+// that publishes a stage.
+__device__ inline void load16_to_lds(int4v rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+__device__ inline void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <int BYTES> struct QWord;
+template <> struct QWord<2> { typedef uint16_t type; };
+template <> struct QWord<4> { typedef uint32_t type; };
+template <> struct QWord<8> { typedef uint64_t type; };
+template <> struct QWord<16> { typedef __uint128_t type; };
+
+// Workgroup = (slab of RW rows i, group g of row tiles {g, mtiles - 1 - g} of H): every
+// workgroup runs the same number of k-steps.  The fold
+//   M_i[a, b] += [Q_ij == a] Z[j, (i, b)]
+// is an outer product per row j, and v_mfma_f32_16x16x1_4b_f32 computes four independent
+// 16 x 16 outer products per instruction, one per group of 16 lanes.  In the 32 x 32
+// accumulator tile lane l holds column l % 32 and register v holds one row j per lane half,
+// so the 16-lane groups are (lane half, 16-column half) and register v itself is the right
+// operand; the left operand is [code of (this lane's row i, that j) == l % C].  With C < 16 a
+// 16-column group spans several rows i and only the diagonal C x C blocks of the 16 x 16
+// result are meaningful; the others are never stored.
 template <int NBITS>
-__global__ __launch_bounds__(256) void t_accum_kernel(const _Float16* __restrict__ Hhi,
-                                                      const _Float16* __restrict__ Hlo,
-                                                      int64_t npad, const uint8_t* __restrict__ Qp,
-                                                      int64_t mpad, int mtiles,
-                                                      float* __restrict__ Apart) {
+__global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __restrict__ Hs,
+                                                           int64_t npad, const uint8_t* __restrict__ Qp,
+                                                           int64_t mpad, int mtiles, int ngroups,
+                                                           float* __restrict__ Apart) {
   constexpr int C = 1 << NBITS;
   constexpr int RW = TN >> NBITS;             // rows i per workgroup
-  constexpr int EPT = (RW * TK) / 256;        // (i, k) positions per thread and stage: 32 >> NBITS
+  constexpr int EPT = (RW * TK) / (64 * TNW); // one-hot positions per thread and stage
+  typedef typename QWord<EPT>::type qword_t;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  auto As_hi = [&](int st) { return reinterpret_cast<_Float16 (*)[TLD]>(smem + st * T_STAGE_BYTES); };
-  auto As_lo = [&](int st) { return reinterpret_cast<_Float16 (*)[TLD]>(smem + st * T_STAGE_BYTES + TM * TLD * 2); };
-  auto Bs_of = [&](int st) { return reinterpret_cast<_Float16 (*)[TLD]>(smem + st * T_STAGE_BYTES + 2 * TM * TLD * 2); };
-  float* Aw = reinterpret_cast<float*>(smem + T_NSTAGE * T_STAGE_BYTES);        // [4][128*C]
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave >> 1, wc = wave & 1;
+  // Workgroups are dealt to the 8 XCDs round-robin by flat index; items are ordered
+  // (group, slab) and each XCD takes a contiguous eighth, so the workgroups sharing an L2
+  // read the same rows of H.
+  const int nslabs = (int)(mpad / RW);
+  const int64_t total = (int64_t)nslabs * ngroups;
+  const int64_t per = (total + 7) / 8;
+  const int64_t qq = blockIdx.x >> 3;
+  const int64_t item = (int64_t)(blockIdx.x & 7) * per + qq;
+  if (qq >= per || item >= total) return;
+  const int group = (int)(item / nslabs);
+  const int64_t i0 = (item % nslabs) * RW;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kh = lane >> 5, l32 = lane & 31;
-  const int64_t i0 = (int64_t)blockIdx.x * RW;
-  const int group = blockIdx.y;
 
-  for (int e = tid; e < 4 * 128 * C; e += 256) Aw[e] = 0.f;
-  for (int st = 0; st < T_NSTAGE; ++st) {
-    _Float16* bz = &Bs_of(st)[0][0];
-    for (int e = tid; e < TN * TLD / 8; e += 256) reinterpret_cast<uint4*>(bz)[e] = uint4{0u, 0u, 0u, 0u};
-  }
+  for (int e = tid; e < T_S * T_STAGEB / 16; e += 64 * TNW)
+    reinterpret_cast<uint4*>(smem)[e] = uint4{0u, 0u, 0u, 0u};
 
   // one-hot staging: this thread owns row il and the EPT consecutive k from kk0 of every stage
   const int ex_il = (tid * EPT) / TK, ex_kk0 = (tid * EPT) % TK;
   const uint8_t* __restrict__ qrow = Qp + (i0 + ex_il) * npad + ex_kk0;
-  int old_code[1][EPT];
+  int old_addr[T_S][EPT];
 #pragma unroll
-  for (int e = 0; e < EPT; ++e) old_code[0][e] = -1;
-  const int lrow = tid >> 2, lk = (tid & 3) * 8;
+  for (int st = 0; st < T_S; ++st)
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) old_addr[st][e] = -1;
+
+  // direct loads of the A tile: one instruction covers 8 rows x 128 bytes
+  const int dr = lane >> 3;
+  const int dc = (lane & 7) ^ dr;
+  uint32_t voff[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+    voff[j] = (uint32_t)(((int64_t)((wave + TNW * j) * 8 + dr) * npad * 4) + dc * 16);
+
+  // fold accumulators: D[jn] = four 16 x 16 blocks (lane half, column half) of column tile jn
+  floatx16 D[2];
+#pragma unroll
+  for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) D[jn][v] = 0.f;
+
+  const int rswzA = l32 & 7, rswzB = (l32 >> 1) & 3;
   __syncthreads();
 
   for (int half = 0; half < 2; ++half) {
     const int mt = (half == 0) ? group : mtiles - 1 - group;
     if (half == 1 && mt == group) break;
     const int64_t jt0 = (int64_t)mt * TM;
-    const int64_t kend = jt0 + TM;            // tiles right of the diagonal are never needed
+    const int nk = (int)((jt0 + TM) / TK);    // tiles right of the diagonal are never needed
 
-    floatx16 acc[2][4];
+    int4v rsA;
+    {
+      const uint64_t ad = (uint64_t)(uintptr_t)(Hs + jt0 * 2 * npad);
+      rsA[0] = (int)(uint32_t)ad;
+      rsA[1] = (int)(uint32_t)((ad >> 32) & 0xffffu);
+      rsA[2] = (int)(uint32_t)((int64_t)TM * npad * 4);
+      rsA[3] = 0x00020000;
+    }
+    auto issue = [&](int k, int st) {
+      const uint32_t soff = (uint32_t)k * 128u;
+      const uint32_t sbase = lds0 + st * T_STAGEB;
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-      for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-
-    // Global operands are fetched two k-steps ahead into two alternating register sets: a
-    // set is written to LDS at the top of its k-step and refilled right away for the k-step
-    // after next, so a load has two MFMA sections to complete.
-    struct Regs {
-      half8 hi[2], lo[2];
-      uint8_t q[EPT];
+      for (int j = 0; j < 2; ++j) load16_to_lds(rsA, sbase + (wave + TNW * j) * 1024, voff[j], soff);
     };
-    auto fetch = [&](Regs& r, int64_t k0) {
-#pragma unroll
-      for (int ps = 0; ps < 2; ++ps) {
-        const int64_t off = (jt0 + lrow + 64 * ps) * npad + k0 + lk;
-        r.hi[ps] = *reinterpret_cast<const half8*>(Hhi + off);
-        r.lo[ps] = *reinterpret_cast<const half8*>(Hlo + off);
-      }
-      if constexpr (EPT == 2) {
-        const uint16_t w = *reinterpret_cast<const uint16_t*>(qrow + k0);
-        r.q[0] = (uint8_t)(w & 0xff); r.q[1] = (uint8_t)(w >> 8);
-      } else if constexpr (EPT == 4) {
-        const uint32_t w = *reinterpret_cast<const uint32_t*>(qrow + k0);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) r.q[e] = (uint8_t)((w >> (8 * e)) & 0xff);
-      } else {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) r.q[e] = qrow[k0 + e];
-      }
-    };
-    _Float16 (*AsHi)[TLD] = As_hi(0);
-    _Float16 (*AsLo)[TLD] = As_lo(0);
-    _Float16 (*Bs)[TLD] = Bs_of(0);
-    auto kstep = [&](Regs& r, int64_t k0) {
-      __syncthreads();                      // every wavefront is done reading the previous stage
-#pragma unroll
-      for (int ps = 0; ps < 2; ++ps) {
-        *reinterpret_cast<half8*>(&AsHi[lrow + 64 * ps][lk]) = r.hi[ps];
-        *reinterpret_cast<half8*>(&AsLo[lrow + 64 * ps][lk]) = r.lo[ps];
-      }
+    auto scatter = [&](qword_t w, int st) {
+      unsigned char* Bs = smem + st * T_STAGEB + T_ATILEB;
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
-        const int code = r.q[e] & (C - 1);
-        if (old_code[0][e] >= 0) Bs[ex_il * C + old_code[0][e]][ex_kk0 + e] = (_Float16)0;
-        Bs[ex_il * C + code][ex_kk0 + e] = (_Float16)1;
-        old_code[0][e] = code;
-      }
-      __syncthreads();
-      if (k0 + 2 * TK < kend) fetch(r, k0 + 2 * TK);
-#pragma unroll
-      for (int ks = 0; ks < TK; ks += 16) {
-        half8 ahi[2], alo[2], bf[4];
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi) {
-          ahi[mi] = *reinterpret_cast<const half8*>(&AsHi[wr * 64 + mi * 32 + l32][ks + 8 * kh]);
-          alo[mi] = *reinterpret_cast<const half8*>(&AsLo[wr * 64 + mi * 32 + l32][ks + 8 * kh]);
-        }
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni)
-          bf[ni] = *reinterpret_cast<const half8*>(&Bs[wc * 128 + ni * 32 + l32][ks + 8 * kh]);
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-          for (int ni = 0; ni < 4; ++ni) {
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi[mi], bf[ni], acc[mi][ni], 0, 0, 0);
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo[mi], bf[ni], acc[mi][ni], 0, 0, 0);
-          }
+        const int code = (int)((w >> (8 * e)) & (C - 1));
+        const int nrow = ex_il * C + code, kk = ex_kk0 + e;
+        const int ad = nrow * T_BROWB + ((((kk >> 3) ^ (nrow >> 1)) & 3) << 4) + (kk & 7) * 2;
+        if (old_addr[st][e] >= 0) *reinterpret_cast<_Float16*>(Bs + old_addr[st][e]) = (_Float16)0;
+        *reinterpret_cast<_Float16*>(Bs + ad) = (_Float16)1;
+        old_addr[st][e] = ad;
       }
     };
-    Regs r0, r1;
-    fetch(r0, 0);
-    if (TK < kend) fetch(r1, TK);
-    for (int64_t k0 = 0; k0 < kend; k0 += 2 * TK) {     // kend is a multiple of 2 TK (TM = 4 TK)
-      kstep(r0, k0);
-      kstep(r1, k0 + TK);
+
+    floatx16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    // stage 0 was last read two barriers ago (nk is even), so it can be refilled at once
+    issue(0, 0);
+    qword_t qw = *reinterpret_cast<const qword_t*>(qrow);
+    scatter(qw, 0);
+    qw = *reinterpret_cast<const qword_t*>(qrow + TK);
+
+    int st = 0;
+#pragma unroll 1
+    for (int k = 0; k < nk; ++k) {
+      wait_all_loads();
+      __syncthreads();
+      if (k + 1 < nk) {
+        issue(k + 1, st ^ 1);
+        if (st == 0) scatter(qw, 1); else scatter(qw, 0);
+        if (k + 2 < nk) qw = *reinterpret_cast<const qword_t*>(qrow + (int64_t)(k + 2) * TK);
+      }
+      const unsigned char* As = smem + st * T_STAGEB;
+      const unsigned char* Bs = As + T_ATILEB;
+#pragma unroll
+      for (int ks = 0; ks < TK / 16; ++ks) {
+        half8 ahi[4], alo[4], bf[2];
+        const int c = 2 * ks + kh;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const unsigned char* rowp = As + (i * 32 + l32) * T_AROWB;
+          ahi[i] = *reinterpret_cast<const half8*>(rowp + ((c ^ rswzA) << 4));
+          alo[i] = *reinterpret_cast<const half8*>(rowp + (((4 + c) ^ rswzA) << 4));
+        }
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn)
+          bf[jn] = *reinterpret_cast<const half8*>(Bs + (wave * 64 + jn * 32 + l32) * T_BROWB + ((c ^ rswzB) << 4));
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int jn = 0; jn < 2; ++jn)
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi[i], bf[jn], acc[i][jn], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int jn = 0; jn < 2; ++jn)
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo[i], bf[jn], acc[i][jn], 0, 0, 0);
+      }
+      st ^= 1;
     }
 
-    // fold: Z[j, (il, b)] -> Aw[wave][il_w][Q[i][j]][b].  The codes of this lane's 32 rows j
-    // are fetched first (8 dwords per row i), so that the loads overlap instead of each
-    // waiting behind an LDS add.
-    float* __restrict__ myA = Aw + wave * 128 * C;
-    uint32_t qd[4][2][4];
+    // fold: register v of tile (i, jn) is row j = i*32 + (v>>2)*8 + kh*4 + (v&3) of the tile
+    const int acmp = lane & (C - 1);
 #pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-      const int ilw = (ni * 32 + l32) >> NBITS;
-      const uint8_t* __restrict__ qr = Qp + (i0 + wc * (RW >> 1) + ilw) * npad + jt0 + wr * 64;
+    for (int i = 0; i < 4; ++i) {
+      uint32_t qd[2][4];
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
+      for (int jn = 0; jn < 2; ++jn) {
+        const int il = (wave * 64 + jn * 32 + l32) >> NBITS;
+        const uint8_t* __restrict__ qr = Qp + (i0 + il) * npad + jt0 + i * 32 + kh * 4;
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq)
-          qd[ni][mi][vq] = *reinterpret_cast<const uint32_t*>(qr + mi * 32 + vq * 8 + kh * 4);
-    }
-    // LDS float atomics are serialised lane by lane on this chip, so the adds are plain
-    // read-modify-writes instead: in each of two passes only the lanes of one half (kh) are
-    // active, which makes every active lane's bin (its own column (il, b), any code a) private
-    // to it; LDS operations of one wavefront execute in program order, so a later step sees
-    // the earlier one's write.  The four column tiles (ni) form independent streams.
-    int base[4];
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni) {
-      const int colw = ni * 32 + l32;                 // pair index within this wave's 128
-      base[ni] = (colw >> NBITS) * C * C + (colw & (C - 1));
-    }
-    for (int pass = 0; pass < 2; ++pass) {
-      if (kh == pass) {
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            // register v of the tile is row mi*32 + (v>>2)*8 + kh*4 + (v&3) of this wave's 64
-            float x[4];
-            int ad[4];
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni) {
-              const int a = (qd[ni][mi][v >> 2] >> (8 * (v & 3))) & (C - 1);
-              ad[ni] = base[ni] + a * C;
-              x[ni] = myA[ad[ni]];
-            }
-#pragma unroll
-            for (int ni = 0; ni < 4; ++ni) myA[ad[ni]] = x[ni] + acc[mi][ni][v];
-          }
+        for (int vq = 0; vq < 4; ++vq) qd[jn][vq] = *reinterpret_cast<const uint32_t*>(qr + vq * 8);
       }
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+#pragma unroll
+        for (int jn = 0; jn < 2; ++jn) {
+          const int code = (int)((qd[jn][v >> 2] >> (8 * (v & 3))) & (C - 1));
+          const float sel = (code == acmp) ? 1.f : 0.f;
+          D[jn] = __builtin_amdgcn_mfma_f32_16x16x1f32(sel, acc[i][jn][v], D[jn], 0, 0, 0);
+        }
     }
-    // the stage that the next row tile writes first may still be read by slower wavefronts
+    // the LDS stages are reused by the next row tile; slower wavefronts may still be reading
     __syncthreads();
   }
-  __syncthreads();
-  // Apart[group][i][a*C + b] = copy(wr = 0) + copy(wr = 1)
-  const int per_half = (RW >> 1) * C * C;    // = 128 * C
-  for (int e = tid; e < RW * C * C; e += 256) {
-    const int wcx = e / per_half, rem = e % per_half;
-    const float v = Aw[(0 * 2 + wcx) * 128 * C + rem] + Aw[(1 * 2 + wcx) * 128 * C + rem];
-    Apart[((int64_t)group * mpad + i0) * C * C + e] = v;
-  }
+
+  // D[jn][4 B + r] = block B = 2 * (lane half of the source) + (16-column half), element
+  // (row 4 (lane / 16) + r, column lane % 16): rows are (i', a), columns (i'', b) within the
+  // 16-column group; keep i' == i'' and add the two lane halves.
+#pragma unroll
+  for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int mrow = 4 * (lane >> 4) + r, ncol = lane & 15;
+        if ((mrow >> NBITS) != (ncol >> NBITS)) continue;
+        const float v = D[jn][4 * ch + r] + D[jn][4 * (2 + ch) + r];
+        const int col = wave * 64 + jn * 32 + ch * 16 + ncol;      // (row i, code b) pair of the slab
+        const int il = col >> NBITS, bb = col & (C - 1), aa = mrow & (C - 1);
+        Apart[((int64_t)group * mpad + i0 + il) * C * C + aa * C + bb] = v;
+      }
 }
 
 // ---- per-row assembly and solve (one wavefront per row, float64) ----
@@ -393,8 +432,7 @@ inline int t_groups(int64_t n) { return (int)((ceil_div(n, TM) + 1) / 2); }
 struct TScratch {
   float* scale;
   float* Hdiag;
-  _Float16* Hhi;
-  _Float16* Hlo;
+  _Float16* Hs;
   uint8_t* Qp;
   float* Apart;
 };
@@ -406,15 +444,13 @@ inline size_t t_layout(int64_t m, int64_t n, int nbits, char* base, TScratch* ou
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   const size_t o_scale = take(2 * sizeof(float));
   const size_t o_diag = take((size_t)n * sizeof(float));
-  const size_t o_hi = take((size_t)npad * npad * sizeof(_Float16));
-  const size_t o_lo = take((size_t)npad * npad * sizeof(_Float16));
+  const size_t o_hs = take((size_t)2 * npad * npad * sizeof(_Float16));
   const size_t o_q = take((size_t)mpad * npad);
   const size_t o_ap = take((size_t)t_groups(n) * mpad * C * C * sizeof(float));
   if (out != nullptr) {
     out->scale = (float*)(base + o_scale);
     out->Hdiag = (float*)(base + o_diag);
-    out->Hhi = (_Float16*)(base + o_hi);
-    out->Hlo = (_Float16*)(base + o_lo);
+    out->Hs = (_Float16*)(base + o_hs);
     out->Qp = (uint8_t*)(base + o_q);
     out->Apart = (float*)(base + o_ap);
   }
@@ -437,7 +473,7 @@ hipError_t launch_t_prepare(hipStream_t s, const float* H, int64_t m, int64_t n,
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(split_lower_kernel, dim3((unsigned)ceil_div(npad, 256), (unsigned)npad),
-                     dim3(256), 0, s, H, n, ldh, npad, sc.scale, sc.Hhi, sc.Hlo);
+                     dim3(256), 0, s, H, n, ldh, npad, sc.scale, sc.Hs);
   return hipGetLastError();
 }
 
@@ -458,19 +494,19 @@ static hipError_t launch_t_accum_n(hipStream_t s, int64_t m, int64_t n, void* sc
   TScratch sc;
   t_layout(m, n, NBITS, (char*)scratch, &sc);
   const int64_t npad = t_npad(n), mpad = t_mpad(m, NBITS);
-  const int C = 1 << NBITS;
   const int mtiles = (int)(npad / TM);
   const int groups = t_groups(n);
-  const size_t shmem = T_NSTAGE * T_STAGE_BYTES + 4 * 128 * C * sizeof(float);
+  const int shmem = T_S * T_STAGEB;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)t_accum_kernel<NBITS>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, shmem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(t_accum_kernel<NBITS>, dim3((unsigned)(mpad / (TN >> NBITS)), (unsigned)groups),
-                     dim3(256), shmem, s, sc.Hhi, sc.Hlo, npad, sc.Qp, mpad, mtiles, sc.Apart);
+  const int64_t total = (mpad / (TN >> NBITS)) * groups;
+  hipLaunchKernelGGL(t_accum_kernel<NBITS>, dim3((unsigned)(8 * ceil_div(total, 8))), dim3(64 * TNW),
+                     shmem, s, sc.Hs, npad, sc.Qp, mpad, mtiles, groups, sc.Apart);
   return hipGetLastError();
 }
 
