@@ -78,14 +78,21 @@ __global__ __launch_bounds__(256) void split_lower_kernel(const float* __restric
   Hs[o + 32] = lo;
 }
 
-// zero-padded, 16-byte aligned copy of Q
+// Zero-padded copy of Q (Qp, one byte per index, read by the fold) and, for the one-hot
+// staging of the GEMM, the byte offset of each index's 1 inside the one-hot LDS tile (Qo):
+// row (i mod RW) * C + code of TK halfs, 16-byte chunks XOR-permuted by (row >> 1) & 3.
 __global__ __launch_bounds__(256) void pad_q_kernel(const uint8_t* __restrict__ Q, int64_t m,
-                                                    int64_t n, int64_t ldq, int64_t npad,
-                                                    uint8_t* __restrict__ Qp) {
+                                                    int64_t n, int64_t ldq, int64_t npad, int nbits,
+                                                    uint8_t* __restrict__ Qp,
+                                                    uint16_t* __restrict__ Qo) {
   const int64_t i = blockIdx.y;
   const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (k >= npad) return;
-  Qp[i * npad + k] = (i < m && k < n) ? Q[i * ldq + k] : (uint8_t)0;
+  const int C = 1 << nbits, RW = TN >> nbits;
+  const int code = (i < m && k < n) ? (Q[i * ldq + k] & (C - 1)) : 0;
+  Qp[i * npad + k] = (uint8_t)code;
+  const int nrow = (int)(i % RW) * C + code, kk = (int)(k & (TK - 1));
+  Qo[i * npad + k] = (uint16_t)(nrow * (TK * 2) + ((((kk >> 3) ^ (nrow >> 1)) & 3) << 4) + (kk & 7) * 2);
 }
 
 // ---- the GEMM with fold epilogue ----
@@ -96,12 +103,13 @@ __global__ __launch_bounds__(256) void pad_q_kernel(const uint8_t* __restrict__ 
 // The one-hot tile is never rebuilt: it starts as zeros and each thread owns a fixed set of
 // (row i, k) positions whose single 1 it moves - it clears the 1 it wrote when the stage
 // was last used and sets the new one (in-order LDS writes of one thread).
-constexpr int T_S = 2;
+constexpr int T_S = 3;
 constexpr int T_AROWB = 128;
 constexpr int T_ATILEB = TM * T_AROWB;
 constexpr int T_BROWB = TK * 2;
 constexpr int T_BTILEB = TN * T_BROWB;
 constexpr int T_STAGEB = T_ATILEB + T_BTILEB;
+constexpr int T_LDS_BYTES = T_S * T_STAGEB;
 
 typedef int int4v __attribute__((ext_vector_type(4)));
 
@@ -114,31 +122,32 @@ __device__ inline void load16_to_lds(int4v rsrc, uint32_t lds_addr, uint32_t vof
 }
 __device__ inline void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-template <int BYTES> struct QWord;
-template <> struct QWord<2> { typedef uint16_t type; };
-template <> struct QWord<4> { typedef uint32_t type; };
-template <> struct QWord<8> { typedef uint64_t type; };
-template <> struct QWord<16> { typedef __uint128_t type; };
+template <int V> struct IntC { static constexpr int value = V; };
 
 // Workgroup = (slab of RW rows i, group g of row tiles {g, mtiles - 1 - g} of H): every
-// workgroup runs the same number of k-steps.  The fold
-//   M_i[a, b] += [Q_ij == a] Z[j, (i, b)]
-// is an outer product per row j, and v_mfma_f32_16x16x1_4b_f32 computes four independent
-// 16 x 16 outer products per instruction, one per group of 16 lanes.  In the 32 x 32
-// accumulator tile lane l holds column l % 32 and register v holds one row j per lane half,
-// so the 16-lane groups are (lane half, 16-column half) and register v itself is the right
-// operand; the left operand is [code of (this lane's row i, that j) == l % C].  With C < 16 a
-// 16-column group spans several rows i and only the diagonal C x C blocks of the 16 x 16
-// result are meaningful; the others are never stored.
+// workgroup runs the same number of k-steps.  Three LDS stages and one barrier per k-step:
+// the barrier at the top of step k publishes the data of step k + 1 and frees the stage of
+// step k - 1, which is refilled for step k + 2; the first MFMA fragments of step k + 1 are
+// read during step k, so no wavefront starts a step waiting for LDS.
+//
+// The fold  M_i[a, b] += [Q_ij == a] Z[j, (i, b)]  is an outer product per row j, and
+// v_mfma_f32_16x16x1_4b_f32 computes four independent 16 x 16 outer products per
+// instruction, one per group of 16 lanes.  In the 32 x 32 accumulator tile lane l holds
+// column l % 32 and register v holds one row j per lane half, so the 16-lane groups are
+// (lane half, 16-column half) and register v itself is the right operand; the left operand
+// is [code of (this lane's row i, that j) == l % C].  With C < 16 a 16-column group spans
+// several rows i and only the diagonal C x C blocks of the 16 x 16 result are meaningful;
+// the others are never stored.
 template <int NBITS>
 __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __restrict__ Hs,
                                                            int64_t npad, const uint8_t* __restrict__ Qp,
+                                                           const uint16_t* __restrict__ Qo,
                                                            int64_t mpad, int mtiles, int ngroups,
                                                            float* __restrict__ Apart) {
   constexpr int C = 1 << NBITS;
   constexpr int RW = TN >> NBITS;             // rows i per workgroup
   constexpr int EPT = (RW * TK) / (64 * TNW); // one-hot positions per thread and stage
-  typedef typename QWord<EPT>::type qword_t;
+  constexpr int EW = EPT / 2;                 // dwords of offsets per thread and stage
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
 
@@ -158,17 +167,28 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __res
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kh = lane >> 5, l32 = lane & 31;
 
-  for (int e = tid; e < T_S * T_STAGEB / 16; e += 64 * TNW)
+  for (int e = tid; e < T_LDS_BYTES / 16; e += 64 * TNW)
     reinterpret_cast<uint4*>(smem)[e] = uint4{0u, 0u, 0u, 0u};
 
-  // one-hot staging: this thread owns row il and the EPT consecutive k from kk0 of every stage
+  // one-hot staging: this thread owns row il and the EPT consecutive k from kk0 of every
+  // stage.  q3..q0 hold the packed tile offsets of the last three scattered steps and of the
+  // next one; the stage written for step s held step s - 3 (stages rotate over all steps of
+  // the workgroup, across both row tiles), so its ones are cleared with q3.  Before the first
+  // steps the "old" positions are this thread's own code-0 positions (zeros already).
   const int ex_il = (tid * EPT) / TK, ex_kk0 = (tid * EPT) % TK;
-  const uint8_t* __restrict__ qrow = Qp + (i0 + ex_il) * npad + ex_kk0;
-  int old_addr[T_S][EPT];
+  const uint32_t* __restrict__ qorow = reinterpret_cast<const uint32_t*>(Qo + (i0 + ex_il) * npad + ex_kk0);
+  uint32_t q3[EW], q2[EW], q1[EW], q0[EW];
 #pragma unroll
-  for (int st = 0; st < T_S; ++st)
+  for (int w = 0; w < EW; ++w) {
+    uint32_t pk = 0;
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) old_addr[st][e] = -1;
+    for (int h = 0; h < 2; ++h) {
+      const int nrow = ex_il * C, kk = ex_kk0 + 2 * w + h;
+      pk |= (uint32_t)(nrow * T_BROWB + ((((kk >> 3) ^ (nrow >> 1)) & 3) << 4) + (kk & 7) * 2) << (16 * h);
+    }
+    q3[w] = q2[w] = q1[w] = pk;
+    q0[w] = pk;
+  }
 
   // direct loads of the A tile: one instruction covers 8 rows x 128 bytes
   const int dr = lane >> 3;
@@ -178,21 +198,18 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __res
   for (int j = 0; j < 2; ++j)
     voff[j] = (uint32_t)(((int64_t)((wave + TNW * j) * 8 + dr) * npad * 4) + dc * 16);
 
-  // fold accumulators: D[jn] = four 16 x 16 blocks (lane half, column half) of column tile jn
-  floatx16 D[2];
-#pragma unroll
-  for (int jn = 0; jn < 2; ++jn)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) D[jn][v] = 0.f;
-
   const int rswzA = l32 & 7, rswzB = (l32 >> 1) & 3;
+  // per-lane LDS byte offsets of the fragments inside a stage
+  const int aoff = l32 * T_AROWB;
+  const int boff = T_ATILEB + (wave * 64 + l32) * T_BROWB;
+  int st = 0;                // stage of the next k-step; rotates over all steps of the workgroup
   __syncthreads();
 
   for (int half = 0; half < 2; ++half) {
     const int mt = (half == 0) ? group : mtiles - 1 - group;
     if (half == 1 && mt == group) break;
     const int64_t jt0 = (int64_t)mt * TM;
-    const int nk = (int)((jt0 + TM) / TK);    // tiles right of the diagonal are never needed
+    const int nk = (int)((jt0 + TM) / TK);    // tiles right of the diagonal are never needed (nk >= 4)
 
     int4v rsA;
     {
@@ -208,16 +225,22 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __res
 #pragma unroll
       for (int j = 0; j < 2; ++j) load16_to_lds(rsA, sbase + (wave + TNW * j) * 1024, voff[j], soff);
     };
-    auto scatter = [&](qword_t w, int st) {
+    auto load_q = [&](int k) {
+#pragma unroll
+      for (int w = 0; w < EW; ++w) q0[w] = qorow[(k * TK) / 2 + w];
+    };
+    // clear the ones of the step that used this stage last (q3), set those of q0, rotate
+    auto scatter = [&](int st) {
       unsigned char* Bs = smem + st * T_STAGEB + T_ATILEB;
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) {
-        const int code = (int)((w >> (8 * e)) & (C - 1));
-        const int nrow = ex_il * C + code, kk = ex_kk0 + e;
-        const int ad = nrow * T_BROWB + ((((kk >> 3) ^ (nrow >> 1)) & 3) << 4) + (kk & 7) * 2;
-        if (old_addr[st][e] >= 0) *reinterpret_cast<_Float16*>(Bs + old_addr[st][e]) = (_Float16)0;
-        *reinterpret_cast<_Float16*>(Bs + ad) = (_Float16)1;
-        old_addr[st][e] = ad;
+      for (int w = 0; w < EW; ++w) {
+        *reinterpret_cast<_Float16*>(Bs + (q3[w] & 0xffffu)) = (_Float16)0;
+        *reinterpret_cast<_Float16*>(Bs + (q3[w] >> 16)) = (_Float16)0;
+        *reinterpret_cast<_Float16*>(Bs + (q0[w] & 0xffffu)) = (_Float16)1;
+        *reinterpret_cast<_Float16*>(Bs + (q0[w] >> 16)) = (_Float16)1;
+        q3[w] = q2[w];
+        q2[w] = q1[w];
+        q1[w] = q0[w];
       }
     };
 
@@ -229,52 +252,80 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __res
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
 
-    // stage 0 was last read two barriers ago (nk is even), so it can be refilled at once
-    issue(0, 0);
-    qword_t qw = *reinterpret_cast<const qword_t*>(qrow);
-    scatter(qw, 0);
-    qw = *reinterpret_cast<const qword_t*>(qrow + TK);
-
-    int st = 0;
-#pragma unroll 1
-    for (int k = 0; k < nk; ++k) {
-      wait_all_loads();
-      __syncthreads();
-      if (k + 1 < nk) {
-        issue(k + 1, st ^ 1);
-        if (st == 0) scatter(qw, 1); else scatter(qw, 0);
-        if (k + 2 < nk) qw = *reinterpret_cast<const qword_t*>(qrow + (int64_t)(k + 2) * TK);
+    struct Frags {
+      half8 ahi[4], alo[4], bf[2];
+    };
+    auto load_frags = [&](Frags& f, int st, int ks) {
+      const unsigned char* S0 = smem + st * T_STAGEB;
+      const int c = 2 * ks + kh;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        f.ahi[i] = *reinterpret_cast<const half8*>(S0 + aoff + i * 32 * T_AROWB + ((c ^ rswzA) << 4));
+        f.alo[i] = *reinterpret_cast<const half8*>(S0 + aoff + i * 32 * T_AROWB + (((4 + c) ^ rswzA) << 4));
       }
-      const unsigned char* As = smem + st * T_STAGEB;
-      const unsigned char* Bs = As + T_ATILEB;
 #pragma unroll
-      for (int ks = 0; ks < TK / 16; ++ks) {
-        half8 ahi[4], alo[4], bf[2];
-        const int c = 2 * ks + kh;
+      for (int jn = 0; jn < 2; ++jn)
+        f.bf[jn] = *reinterpret_cast<const half8*>(S0 + boff + jn * 32 * T_BROWB + ((c ^ rswzB) << 4));
+    };
+    auto mma = [&](const Frags& f) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const unsigned char* rowp = As + (i * 32 + l32) * T_AROWB;
-          ahi[i] = *reinterpret_cast<const half8*>(rowp + ((c ^ rswzA) << 4));
-          alo[i] = *reinterpret_cast<const half8*>(rowp + (((4 + c) ^ rswzA) << 4));
-        }
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn)
-          bf[jn] = *reinterpret_cast<const half8*>(Bs + (wave * 64 + jn * 32 + l32) * T_BROWB + ((c ^ rswzB) << 4));
+          acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.ahi[i], f.bf[jn], acc[i][jn], 0, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int jn = 0; jn < 2; ++jn)
-            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ahi[i], bf[jn], acc[i][jn], 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int jn = 0; jn < 2; ++jn)
-            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(alo[i], bf[jn], acc[i][jn], 0, 0, 0);
-      }
-      st ^= 1;
-    }
+        for (int jn = 0; jn < 2; ++jn)
+          acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.alo[i], f.bf[jn], acc[i][jn], 0, 0, 0);
+    };
 
-    // fold: register v of tile (i, jn) is row j = i*32 + (v>>2)*8 + kh*4 + (v&3) of the tile
+    // every stage is free here (start of the kernel, or the barrier after the previous fold)
+    {
+      const int st1 = (st == 2) ? 0 : st + 1;
+      load_q(0);
+      issue(0, st);
+      issue(1, st1);
+      scatter(st);
+      load_q(1);
+      scatter(st1);
+      load_q(2);
+    }
+    wait_all_loads();
+    __syncthreads();
+    Frags f0, f1;
+    load_frags(f0, st, 0);   // step 0 repeats the barrier, which costs nothing here
+
+    // One k-step.  PRODUCE: stage the operands of step k + 2 (the Q offsets of step k + 3
+    // are fetched with a clamped index so that the load is unconditional).  PREFETCH: read
+    // the first fragments of step k + 1.
+    auto step = [&](int k, auto PRODUCE, auto PREFETCH) {
+      const int st1 = (st == 2) ? 0 : st + 1, st2 = (st == 0) ? 2 : st - 1;
+      wait_all_loads();
+      __syncthreads();
+      if constexpr (decltype(PRODUCE)::value != 0) {
+        scatter(st2);
+        load_q(k + 3 < nk ? k + 3 : nk - 1);
+        issue(k + 2, st2);
+      }
+      load_frags(f1, st, 1);
+      mma(f0);
+      if constexpr (decltype(PREFETCH)::value != 0) load_frags(f0, st1, 0);
+      mma(f1);
+      st = st1;
+    };
+#pragma unroll 1
+    for (int k = 0; k < nk - 2; ++k) step(k, IntC<1>{}, IntC<1>{});
+    step(nk - 2, IntC<0>{}, IntC<1>{});
+    step(nk - 1, IntC<0>{}, IntC<0>{});
+
+    // fold: register v of tile (i, jn) is row j = i*32 + (v>>2)*8 + kh*4 + (v&3) of the tile.
+    // D[jn] = four 16 x 16 blocks (lane half, column half) of column tile jn.
+    floatx16 D[2];
+#pragma unroll
+    for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) D[jn][v] = 0.f;
     const int acmp = lane & (C - 1);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -290,31 +341,33 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __res
       for (int v = 0; v < 16; ++v)
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn) {
-          const int code = (int)((qd[jn][v >> 2] >> (8 * (v & 3))) & (C - 1));
+          const int code = (int)((qd[jn][v >> 2] >> (8 * (v & 3))) & 0xffu);
           const float sel = (code == acmp) ? 1.f : 0.f;
           D[jn] = __builtin_amdgcn_mfma_f32_16x16x1f32(sel, acc[i][jn][v], D[jn], 0, 0, 0);
         }
     }
+    // D[jn][4 B + r] = block B = 2 * (lane half of the source) + (16-column half), element
+    // (row 4 (lane / 16) + r, column lane % 16): rows are (i', a), columns (i'', b) within the
+    // 16-column group; keep i' == i'' and add the two lane halves.  The second row tile adds
+    // to what this same thread stored after the first.
+#pragma unroll
+    for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int mrow = 4 * (lane >> 4) + r, ncol = lane & 15;
+          if ((mrow >> NBITS) != (ncol >> NBITS)) continue;
+          float v = D[jn][4 * ch + r] + D[jn][4 * (2 + ch) + r];
+          const int col = wave * 64 + jn * 32 + ch * 16 + ncol;      // (row i, code b) pair of the slab
+          const int il = col >> NBITS, bb = col & (C - 1), aa = mrow & (C - 1);
+          float* dst = Apart + ((int64_t)group * mpad + i0 + il) * C * C + aa * C + bb;
+          if (half == 1) v += *dst;
+          *dst = v;
+        }
     // the LDS stages are reused by the next row tile; slower wavefronts may still be reading
     __syncthreads();
   }
-
-  // D[jn][4 B + r] = block B = 2 * (lane half of the source) + (16-column half), element
-  // (row 4 (lane / 16) + r, column lane % 16): rows are (i', a), columns (i'', b) within the
-  // 16-column group; keep i' == i'' and add the two lane halves.
-#pragma unroll
-  for (int jn = 0; jn < 2; ++jn)
-#pragma unroll
-    for (int ch = 0; ch < 2; ++ch)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int mrow = 4 * (lane >> 4) + r, ncol = lane & 15;
-        if ((mrow >> NBITS) != (ncol >> NBITS)) continue;
-        const float v = D[jn][4 * ch + r] + D[jn][4 * (2 + ch) + r];
-        const int col = wave * 64 + jn * 32 + ch * 16 + ncol;      // (row i, code b) pair of the slab
-        const int il = col >> NBITS, bb = col & (C - 1), aa = mrow & (C - 1);
-        Apart[((int64_t)group * mpad + i0 + il) * C * C + aa * C + bb] = v;
-      }
 }
 
 // ---- per-row assembly and solve (one wavefront per row, float64) ----
@@ -434,6 +487,7 @@ struct TScratch {
   float* Hdiag;
   _Float16* Hs;
   uint8_t* Qp;
+  uint16_t* Qo;
   float* Apart;
 };
 
@@ -446,12 +500,14 @@ inline size_t t_layout(int64_t m, int64_t n, int nbits, char* base, TScratch* ou
   const size_t o_diag = take((size_t)n * sizeof(float));
   const size_t o_hs = take((size_t)2 * npad * npad * sizeof(_Float16));
   const size_t o_q = take((size_t)mpad * npad);
+  const size_t o_qo = take((size_t)mpad * npad * sizeof(uint16_t));
   const size_t o_ap = take((size_t)t_groups(n) * mpad * C * C * sizeof(float));
   if (out != nullptr) {
     out->scale = (float*)(base + o_scale);
     out->Hdiag = (float*)(base + o_diag);
     out->Hs = (_Float16*)(base + o_hs);
     out->Qp = (uint8_t*)(base + o_q);
+    out->Qo = (uint16_t*)(base + o_qo);
     out->Apart = (float*)(base + o_ap);
   }
   return off;
@@ -484,7 +540,7 @@ hipError_t launch_t_pad(hipStream_t s, const uint8_t* Q, int64_t m, int64_t n, i
   t_layout(m, n, nbits, (char*)scratch, &sc);
   const int64_t npad = t_npad(n), mpad = t_mpad(m, nbits);
   hipLaunchKernelGGL(pad_q_kernel, dim3((unsigned)ceil_div(npad, 256), (unsigned)mpad), dim3(256), 0,
-                     s, Q, m, n, ldq, npad, sc.Qp);
+                     s, Q, m, n, ldq, npad, nbits, sc.Qp, sc.Qo);
   return hipGetLastError();
 }
 
@@ -496,7 +552,7 @@ static hipError_t launch_t_accum_n(hipStream_t s, int64_t m, int64_t n, void* sc
   const int64_t npad = t_npad(n), mpad = t_mpad(m, NBITS);
   const int mtiles = (int)(npad / TM);
   const int groups = t_groups(n);
-  const int shmem = T_S * T_STAGEB;
+  const int shmem = T_LDS_BYTES;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)t_accum_kernel<NBITS>,
@@ -506,7 +562,7 @@ static hipError_t launch_t_accum_n(hipStream_t s, int64_t m, int64_t n, void* sc
   }
   const int64_t total = (mpad / (TN >> NBITS)) * groups;
   hipLaunchKernelGGL(t_accum_kernel<NBITS>, dim3((unsigned)(8 * ceil_div(total, 8))), dim3(64 * TNW),
-                     shmem, s, sc.Hs, npad, sc.Qp, mpad, mtiles, groups, sc.Apart);
+                     shmem, s, sc.Hs, npad, sc.Qp, sc.Qo, mpad, mtiles, groups, sc.Apart);
   return hipGetLastError();
 }
 
