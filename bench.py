@@ -33,6 +33,23 @@ PEAK_F32_MFMA_TFLOPS = 157.3
 PEAK_F32_ADD_TOPS = 78.6
 
 
+# HBM bytes per launch on config c3 (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc, each scaled by the
+# reading of a plain 1 GiB copy: x2.000 and x1.000); copied from profiles/bench_c3_hbm_traffic.txt,
+# which gives the commands.  Other configs report null.
+TRAFFIC_C3_BYTES = {
+    "hessian": (18130.93 + 513.00 + 516.05 + 64.09) * 2 ** 20,     # product kernel + reduction
+    "update_s": 1994.91 * 2 ** 20,
+    "t_accum": 819.93 * 2 ** 20,
+    "t_solve": 265.70 * 2 ** 20,
+    "t_pad": 64.02 * 2 ** 20,
+    "gemm_wh": 806.44 * 2 ** 20,
+    "loss": (806.44 + 146.03 + 128.15) * 2 ** 20,
+    "init": (96.02 + 64.30) * 2 ** 20,
+    "cholesky": (96.27 + 126 * 13.26 + 64 * 0.06) * 2 ** 20,
+    "t_prep": (65.24 + 0.52) * 2 ** 20,
+}
+
+
 def kernel_work(cls, m, n, p, nbits, iters):
     """Algorithmic work of ONE launch of a kernel class: (bound, work, unit, peak)."""
     if cls == "hessian":
@@ -98,6 +115,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy before the timed region: under "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE its reading gives the scale of the counter")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the solver has no multi-GPU path); "
@@ -128,6 +148,12 @@ def main():
         state["loss"] = ctx.layer_loss(Wf, H, T, Q, cfg.nbits)
         state["T"] = T
 
+    if args.calibrate_copy:
+        calib = torch.zeros(2, 1 << 28, dtype=torch.float32, device=dev)    # 2 x 1 GiB
+        torch.cuda.synchronize()
+        calib[1].copy_(calib[0])                                            # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del calib
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -150,11 +176,12 @@ def main():
         rate = work / (avg_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9) if avg_ms > 0 else 0.0
         kernels[cls] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps,
                         "avg_ms": avg_ms, "bound": bound, "achieved": rate, "peak": peak, "unit": unit,
-                        "frac": rate / peak}
+                        "frac": rate / peak,
+                        "traffic": TRAFFIC_C3_BYTES.get(cls) if cfg.name == "c3" else None}
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     kd = kernels[dominant]
     roofline = {"kernel": dominant, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
-                "unit": kd["unit"], "frac": kd["frac"], "traffic": None,
+                "unit": kd["unit"], "frac": kd["frac"], "traffic": kd["traffic"],
                 "avg_launch_ms": kd["avg_ms"]}
 
     out = {

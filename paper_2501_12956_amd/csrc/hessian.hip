@@ -59,17 +59,16 @@ __global__ __launch_bounds__(64 * HNW) void hessian_f16_kernel(const _Float16* _
                                                               int64_t p, int64_t ldx, int64_t chunk,
                                                               int ntiles, int nsplit,
                                                               float* __restrict__ partials) {
-  // Workgroups are dealt to the 8 XCDs round-robin by their flat index.  Work items are
-  // ordered (split, tile) and each XCD takes a contiguous eighth of that list, so that the
-  // workgroups sharing an L2 stream the same token range and neighbouring row blocks of X.
-  const int64_t total = (int64_t)ntiles * nsplit;
-  const int64_t per = (total + 7) / 8;
-  const int64_t q = blockIdx.x >> 3;
-  const int64_t item = (int64_t)(blockIdx.x & 7) * per + q;
-  if (q >= per || item >= total) return;
-  const int split = (int)(item / ntiles);
+  // Workgroups are dealt to the 8 XCDs round-robin by their flat index.  All XCDs work on
+  // the same token split at the same time, so that the slice of X in flight fits the
+  // memory-side cache, and XCD x takes a contiguous run of the split's tiles, which share
+  // row blocks of X through its L2.
+  const int tpx = (ntiles + 7) / 8;
+  const int q = blockIdx.x >> 3, xcd = blockIdx.x & 7;
+  const int split = q / tpx;
   // triangular tile index -> (bm, bn), bn <= bm
-  const int t = (int)(item % ntiles);
+  const int t = xcd * tpx + q % tpx;
+  if (split >= nsplit || t >= ntiles) return;
   int bm = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
   while ((int64_t)(bm + 1) * (bm + 2) / 2 <= t) ++bm;
   while ((int64_t)bm * (bm + 1) / 2 > t) --bm;
@@ -180,7 +179,19 @@ __global__ __launch_bounds__(256) void reduce_mirror_kernel(float* __restrict__ 
     const int64_t i = (int64_t)bi * 32 + r, j = (int64_t)bj * 32 + tx;
     float v = 0.f;
     if (i < n && j < n && j <= i) {
-      for (int s = 0; s < nsplit; ++s) v += src[(int64_t)s * lds * n + i * lds + j];
+      // four independent running sums keep several loads in flight; the order is fixed
+      const float* __restrict__ sp = src + i * lds + j;
+      const int64_t ss = lds * n;
+      float v0 = 0.f, v1 = 0.f, v2 = 0.f, v3 = 0.f;
+      int s = 0;
+      for (; s + 4 <= nsplit; s += 4) {
+        v0 += sp[(int64_t)s * ss];
+        v1 += sp[(int64_t)(s + 1) * ss];
+        v2 += sp[(int64_t)(s + 2) * ss];
+        v3 += sp[(int64_t)(s + 3) * ss];
+      }
+      for (; s < nsplit; ++s) v0 += sp[(int64_t)s * ss];
+      v = (v0 + v1) + (v2 + v3);
       if (accumulate) v += H[i * ldh + j];
       H[i * ldh + j] = v;
     }
@@ -217,7 +228,7 @@ hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64
   int64_t chunk = ceil_div(ceil_div(p, split), HK) * HK;
   const int64_t nt = ceil_div(n, HT);
   const int ntiles = (int)(nt * (nt + 1) / 2);
-  dim3 grid((unsigned)(8 * ceil_div((int64_t)ntiles * split, 8)));
+  dim3 grid((unsigned)(8 * ceil_div(ntiles, 8) * split));
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t ea = hipFuncSetAttribute((const void*)hessian_f16_kernel,
