@@ -1,10 +1,15 @@
 // L = Cholesky(H) or of its preconditioned form (Eq. (10), Remark 3.1,
-// Appendix A Eq. (23)-(24)), blocked right-looking, fp32 storage.
+// Appendix A Eq. (23)-(24)), blocked, fp32 storage.
 //
-// Per 64-column panel: (1) the 64 x 64 diagonal block is factored, and the
-// factor inverted, by one wavefront; (2) the rows below it are multiplied by
-// that inverse (matrix-core GEMM, in place); (3) the trailing lower triangle is
-// updated with the fp32 matrix-core GEMM (A A^T form).
+// The lower triangle of H (plus the preconditioner) is copied to a working matrix W; L is
+// written once and never read back as input of the same kernel that writes it.  Columns go
+// in outer panels of 256, each of four inner blocks of 64:
+//   inner block (one launch): every workgroup owns 64 rows below the diagonal block and
+//     repeats the small shared part itself - it brings the 64 x 64 diagonal block up to date
+//     with the earlier inner blocks of the panel (left-looking, from L), factors it and
+//     inverts the factor in LDS - then updates its own rows the same way and multiplies
+//     them by that inverse.  No second launch and no grid-wide dependency for the solve.
+//   outer panel: W22 -= L21 L21^T with K = 256 on the fp32 matrix-core GEMM.
 #include "ganq_internal.h"
 
 namespace ganq {
@@ -14,24 +19,24 @@ constexpr int NB = 64;
 
 __global__ void fill_i32_kernel(int* p, int v) { *p = v; }
 
-// L <- lower triangle of H (+ preconditioner on the diagonal), strict upper zeroed.
+// W <- lower triangle of H (+ preconditioner on the diagonal), L <- 0.
 // delta (if used) must already hold the diagonal offsets.
 __global__ __launch_bounds__(256) void copy_lower_kernel(const float* __restrict__ H, int64_t n,
-                                                         int64_t ldh, float* __restrict__ L,
-                                                         int64_t ldl, int precond, float lambda,
+                                                         int64_t ldh, float* __restrict__ W,
+                                                         float* __restrict__ L, int64_t ldl,
+                                                         int precond, float lambda,
                                                          const float* __restrict__ delta) {
   const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t i = blockIdx.y;
   if (j >= n) return;
-  float v = 0.f;
-  if (j <= i) {
-    v = H[i * ldh + j];
-    if (j == i) {
-      if (precond == GANQ_PRECOND_LAMBDA) v += lambda;
-      if (precond == GANQ_PRECOND_DIAGDOM) v += delta[i];
-    }
+  L[i * ldl + j] = 0.f;
+  if (j > i) return;
+  float v = H[i * ldh + j];
+  if (j == i) {
+    if (precond == GANQ_PRECOND_LAMBDA) v += lambda;
+    if (precond == GANQ_PRECOND_DIAGDOM) v += delta[i];
   }
-  L[i * ldl + j] = v;
+  W[i * n + j] = v;
 }
 
 // delta_i = max(sum_j |H_ij| - 2 H_ii, 1e-8), Appendix A Eq. (23); one workgroup per row.
@@ -53,124 +58,352 @@ __global__ __launch_bounds__(256) void diagdom_delta_kernel(const float* __restr
   }
 }
 
-// Factor the nb x nb diagonal block at (k0, k0) in place and write the inverse of the factor
-// (64 x 64, fp32, row-major, identity-padded beyond nb) to `inv`.
+// ---- 64 x 64 diagonal block: factor and inverse of the factor, one workgroup ----
 //
-// Thread (r, g) = (tid / 4, tid % 4) keeps the entries (r, g + 4 i) of ONE 64 x 64 working
-// matrix M in registers.  Columns right of the current one hold the not yet factored part
-// of A; columns left of it are reused for the right-hand sides of L X = I (column k of L
-// is dead once step k has used it and is copied out to LDS).  Step k is a single rank-1
-// update  M[r][:] -= L[r][k] * v  for r > k  with  v = ( X[k][0..k-1], 1/L_kk, L[k+1..][k] ),
-// one barrier per step (publish buffers are double-buffered).  On a bad pivot the 1-based
-// global index of the first one is recorded in *info (if still 0) and the pivot is replaced
-// by 1 so that the kernel terminates normally.
-// The 64 steps run as 16 iterations of 4 unrolled steps (the unrolled 64 would not fit the
-// instruction cache).  The register array is rotated by one after every 4 steps so that
-// a[0] always holds the entry of the current column group ik: a[i] is column
-// g + 4 ((ik + i) mod 16); positions i >= 16 - ik are columns already factored (they hold
-// the inverse), positions 1 .. 15 - ik are columns still to come.
-template <int GK>
-__device__ inline void potf_step(float (&a)[16], int ik, int r, int g, int nb, int64_t k0,
-                                 int* __restrict__ info, float (*vbuf)[NB], float* __restrict__ piv,
-                                 float (*Lout)[NB + 1]) {
-  constexpr int bf = GK & 1;
-  const int K = 4 * ik + GK;
-  // Publish the raw vector  v = ( M[K][c] for c < K, 1 at c == K, M[c][K] for c > K )  in
-  // the readers' register order: entry c at [(c & 3) * 16 + ((c / 4 - ik) mod 16)], i.e.
-  // thread (., g) finds the entries of its 16 registers at [16 g .. 16 g + 15].
-  if (r == K) {
-#pragma unroll
-    for (int i = 1; i < 16; ++i)
-      if (i >= 16 - ik) vbuf[bf][g * 16 + i] = a[i];       // columns already factored
-    if (g < GK) vbuf[bf][g * 16] = a[0];
-    if (g == GK) {
-      vbuf[bf][g * 16] = 1.f;
-      piv[bf] = a[0];
-    }
-  } else if (r > K && g == GK) {
-    vbuf[bf][(r & 3) * 16 + (((r >> 2) - ik) & 15)] = a[0];
+// The block lives in LDS and is processed as 4 x 4 leaves of 16 x 16.  Per leaf column kb:
+// (a) one wavefront factors the 16 x 16 diagonal leaf with its rows in lanes 0..15 and its
+//     columns in registers - pivots and multipliers travel by v_readlane, no LDS round trip
+//     and no barrier inside the 16 steps - and inverts the leaf factor by forward
+//     substitution (one column per lane);
+// (b) all threads form the leaf panel below it, P = A21 * inv(L11)^T;
+// (c) all threads apply  A22 -= P P^T  to the rest of the block.
+// The inverse of the whole 64 x 64 factor is then assembled from the leaf inverses by block
+// forward substitution, one block diagonal per level.  Three barriers per leaf column and two
+// per level instead of one per matrix column.  On a bad pivot the 1-based global index of
+// the first one is recorded in *info (if still 0) and the pivot is replaced by 1 so that
+// the kernel terminates normally.
+constexpr int BLD = NB + 1;    // LDS row stride (floats)
+
+// value of lane LANE of the same row of 16 lanes (DPP row broadcast, folds into the consumer)
+template <int LANE>
+__device__ inline float row_bcast(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x150 + LANE,
+                                                                0xf, 0xf, true));
+}
+
+// acc += bcast * y, where bcast is x of lane LANE of the same row of 16 lanes: one VOP2 DPP
+// instruction.  The caller separates the write of x from the first such read by two wait
+// states (dpp_wait), which the compiler does not do for inline assembly.
+template <int LANE>
+__device__ inline void fmac_row_bcast(float& acc, float x, float y) {
+  asm volatile("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+               : "+v"(acc) : "v"(x), "v"(y), "n"(LANE));
+}
+// two wait states between the (earlier) write of v and its (later) DPP reads
+__device__ inline void dpp_wait(float& v) { asm volatile("s_nop 1" : "+v"(v)); }
+
+template <int K, int C>
+struct LeafCols {
+  static __device__ inline void update(float (&a)[16], float lk, float nlk) {
+    fmac_row_bcast<C>(a[C], lk, nlk);               // a[C] -= L[C][K] * L[r][K]
+    LeafCols<K, C + 1>::update(a, lk, nlk);
   }
-  __syncthreads();
-  float d = piv[bf];
-  if (!(d > 0.f) || !(d < 3.0e38f)) {
-    if (r == 0 && g == 0 && K < nb) atomicCAS(info, 0, (int)(k0 + K + 1));
-    d = 1.f;
+};
+template <int K>
+struct LeafCols<K, 16> {
+  static __device__ inline void update(float (&)[16], float, float) {}
+};
+
+template <int K>
+struct LeafSteps {
+  // branch-free: a bad pivot (not positive, or not finite) is replaced by 1 and the first
+  // such column of the leaf is remembered in badk
+  static __device__ inline void run(float (&a)[16], float (&rsv)[16], int r, int& badk) {
+    dpp_wait(a[K]);                                   // written by the previous step's DPP FMA
+    float piv = row_bcast<K>(a[K]);
+    const bool bad = !(piv > 0.f) || !(piv < 3.0e38f);
+    badk = (bad && badk == 16) ? K : badk;
+    piv = bad ? 1.f : piv;
+    const float rs = __builtin_amdgcn_rsqf(piv);      // 1 ulp
+    rsv[K] = rs;
+    const float akk = (bad && r == K) ? 1.f : a[K];
+    float lk = (r >= K) ? akk * rs : 0.f;             // L[r][K]; row K gets piv * rs = sqrt(piv)
+    a[K] = lk;
+    const float nlk = -lk;
+    dpp_wait(lk);
+    LeafCols<K, K + 1>::update(a, lk, nlk);
+    LeafSteps<K + 1>::run(a, rsv, r, badk);
   }
-  const float sd = sqrtf(d);
-  const float rs = 1.f / sd;
-  const float lraw = vbuf[bf][(r & 3) * 16 + (((r >> 2) - ik) & 15)];   // M[r][K] for r > K
-  if (g == GK) Lout[r][K] = (r == K) ? sd : ((r > K) ? lraw * rs : 0.f);
-  // rows r > K: M[r][c] -= L[r][K] * (v[c] / L_KK)  (the entry at c == K starts from 0);
-  // row K: M[K][c] = v[c] / L_KK (its part of the inverse is final); rows r < K: unchanged.
-  // Entries above the diagonal receive harmless finite values that nothing reads.
-  const float coef = (r > K) ? -(lraw * rs) * rs : ((r == K) ? rs : 0.f);
-  const bool zero_row = (r == K);
+};
+template <>
+struct LeafSteps<16> {
+  static __device__ inline void run(float (&)[16], float (&)[16], int, int&) {}
+};
+
+// Forward substitution L x = e_j with one column j per lane: once x[K] is known every later
+// row's running sum takes its term, s[RR] -= L[RR][K] x[K] (independent instructions).
+template <int K, int RR>
+struct LeafInvRows {
+  static __device__ inline void update(const float (&a)[16], float (&sv)[16], float nx) {
+    fmac_row_bcast<RR>(sv[RR], a[K], nx);            // a[K] of lane RR is L[RR][K]
+    LeafInvRows<K, RR + 1>::update(a, sv, nx);
+  }
+};
+template <int K>
+struct LeafInvRows<K, 16> {
+  static __device__ inline void update(const float (&)[16], float (&)[16], float) {}
+};
+template <int K>
+struct LeafInv {
+  static __device__ inline void run(const float (&a)[16], const float (&rsv)[16], float (&sv)[16]) {
+    sv[K] *= rsv[K];                                 // x[K]
+    const float nx = -sv[K];
+    LeafInvRows<K, K + 1>::update(a, sv, nx);
+    LeafInv<K + 1>::run(a, rsv, sv);
+  }
+};
+template <>
+struct LeafInv<16> {
+  static __device__ inline void run(const float (&)[16], const float (&)[16], float (&)[16]) {}
+};
+
+// rows o .. o+15 of M, wavefront 0 only: every row of 16 lanes works on the same leaf (lane
+// l holds matrix row l % 16, its 16 columns in registers); lanes 0..15 store the result.
+// Pivots and multipliers travel between lanes by DPP row broadcasts.
+__device__ inline void factor_leaf(float (*M)[BLD], float (*Inv)[BLD], int o, int nb, int64_t k0,
+                                   int* __restrict__ info) {
+  const int lane = threadIdx.x & 63, r = lane & 15;
+  float a[16], rsv[16], x[16];
 #pragma unroll
-  for (int i4 = 0; i4 < 4; ++i4) {
-    const float4 vv = *reinterpret_cast<const float4*>(&vbuf[bf][g * 16 + 4 * i4]);
-    const float ve[4] = {vv.x, vv.y, vv.z, vv.w};
+  for (int c = 0; c < 16; ++c) a[c] = M[o + r][o + c];
+  int badk = 16;
+  LeafSteps<0>::run(a, rsv, r, badk);
+  if (badk < 16 && lane == 0 && o + badk < nb) atomicCAS(info, 0, (int)(k0 + o + badk + 1));
+  // inverse of the leaf factor: lane j solves L x = e_j
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int i = 4 * i4 + e;
-      const bool zero_in = zero_row || (i == 0 && g == GK);
-      a[i] = fmaf(coef, ve[e], zero_in ? 0.f : a[i]);
+  for (int c = 0; c < 16; ++c) x[c] = (c == r) ? 1.f : 0.f;
+  LeafInv<0>::run(a, rsv, x);
+  if (lane < 16) {
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      M[o + r][o + c] = a[c];
+      Inv[o + c][o + r] = x[c];
     }
   }
 }
 
-__global__ __launch_bounds__(256) void potf2_inv_kernel(float* __restrict__ L, int64_t ldl,
-                                                        int64_t k0, int nb, int* __restrict__ info,
-                                                        float* __restrict__ inv) {
-  __shared__ float Lout[NB][NB + 1];
-  __shared__ __attribute__((aligned(16))) float vbuf[2][NB];
-  __shared__ float piv[2];
-  const int tid = threadIdx.x, r = tid >> 2, g = tid & 3;
-  // coalesced load through LDS (identity padding beyond nb, strict upper part zero)
-  for (int e = tid; e < NB * NB; e += 256) {
-    const int rr = e >> 6, cc = e & 63;
-    float v = (rr == cc) ? 1.f : 0.f;
-    if (rr < nb && cc < nb) v = (cc <= rr) ? L[(k0 + rr) * ldl + k0 + cc] : 0.f;
-    Lout[rr][cc] = v;
+// M: the block (lower triangle meaningful on entry, identity beyond nb); on exit its lower
+// triangle is the factor (strict upper part of the leaves zero) and Inv its inverse (lower).
+// Tmp is scratch.  256 threads; ends with a barrier.  The 16 x 16 leaf products run on the
+// matrix cores (v_mfma_f32_16x16x4_f32: lane l supplies A[l % 16][l / 16] and
+// B[l / 16][l % 16] and receives D[4 (l / 16) + r][l % 16], r = 0..3).
+__device__ inline void factor_block(float (*M)[BLD], float (*Inv)[BLD], float (*Tmp)[BLD], int nb,
+                                    int64_t k0, int* __restrict__ info) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lm = lane & 15, lk = lane >> 4;
+  for (int e = tid; e < NB * NB; e += 256) Inv[e >> 6][e & 63] = 0.f;
+  __syncthreads();
+  for (int kb = 0; kb < 4; ++kb) {
+    const int o = 16 * kb;
+    if (wave == 0) factor_leaf(M, Inv, o, nb, k0, info);
+    __syncthreads();
+    const int tiles = 3 - kb;             // 16-row tiles under the leaf
+    // (b) P = A21 * inv(L11)^T, one row tile per wavefront, in place (a wavefront reads only
+    // its own rows of M before it writes them)
+    if (wave < tiles) {
+      const int r0 = o + 16 + 16 * wave;
+      floatx4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 16; kk += 4)
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(M[r0 + lm][o + kk + lk], Inv[o + lm][o + kk + lk], d, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) M[r0 + 4 * lk + r][o + lm] = d[r];
+    }
+    __syncthreads();
+    // (c) A22 -= P P^T on the leaf tiles (ti, tj), tj <= ti
+    for (int t = wave; t < tiles * (tiles + 1) / 2; t += 4) {
+      int ti = 0;
+      while ((ti + 1) * (ti + 2) / 2 <= t) ++ti;
+      const int tj = t - ti * (ti + 1) / 2;
+      const int r0 = o + 16 + 16 * ti, c0 = o + 16 + 16 * tj;
+      floatx4 d;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) d[r] = M[r0 + 4 * lk + r][c0 + lm];
+#pragma unroll
+      for (int kk = 0; kk < 16; kk += 4)
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(-M[r0 + lm][o + kk + lk], M[c0 + lm][o + kk + lk], d, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) M[r0 + 4 * lk + r][c0 + lm] = d[r];
+    }
+    __syncthreads();
+  }
+  // inverse of the 64 x 64 factor: Inv_ij = -Inv_ii * sum_{k=j}^{i-1} L_ik Inv_kj for i - j = d,
+  // one leaf (i, j) per wavefront and level
+  for (int d = 1; d < 4; ++d) {
+    const int j = wave, i = wave + d;
+    if (i < 4) {
+      floatx4 t = {0.f, 0.f, 0.f, 0.f};
+      for (int q = 16 * j; q < 16 * i; q += 4)
+        t = __builtin_amdgcn_mfma_f32_16x16x4f32(M[16 * i + lm][q + lk], Inv[q + lk][16 * j + lm], t, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) Tmp[16 * i + 4 * lk + r][16 * j + lm] = t[r];
+      // same wavefront reads it back as the right operand (LDS operations of a wavefront are in order)
+      floatx4 x = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 16; kk += 4)
+        x = __builtin_amdgcn_mfma_f32_16x16x4f32(-Inv[16 * i + lm][16 * i + kk + lk], Tmp[16 * i + kk + lk][16 * j + lm], x, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) Inv[16 * i + 4 * lk + r][16 * j + lm] = x[r];
+    }
+    __syncthreads();
+  }
+}
+
+// acc (a 16 x 64 strip: rows 16 wave .., tile t = columns 16 t ..) += sign * A B^T over K
+// columns, A and B row-major in LDS with odd strides (conflict-free operand reads).
+__device__ inline void strip_mma(floatx4 (&acc)[4], const float* __restrict__ A, int lda,
+                                 const float* __restrict__ B, int ldb, int K, int wave, int lm, int lk,
+                                 float sign) {
+  for (int k4 = 0; k4 < K; k4 += 4) {
+    const float av = sign * A[(16 * wave + lm) * lda + k4 + lk];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, B[(16 * t + lm) * ldb + k4 + lk], acc[t], 0, 0, 0);
+  }
+}
+
+constexpr int PLD = 3 * NB + 1;   // LDS stride of the diagonal rows' earlier columns
+
+// Inner block at columns c0 .. c0 + nb of the outer panel that starts at column J.
+// Workgroup w owns rows c0 + 64 + 64 w .. (if any); workgroup 0 also stores the diagonal block.
+__global__ __launch_bounds__(256) void chol_panel_kernel(const float* __restrict__ W, float* __restrict__ L,
+                                                         int64_t ldl, int64_t n, int64_t J, int64_t c0,
+                                                         int nb, int* __restrict__ info) {
+  extern __shared__ __attribute__((aligned(16))) float psm[];
+  float (*M)[BLD] = reinterpret_cast<float (*)[BLD]>(psm);
+  float (*Inv)[BLD] = reinterpret_cast<float (*)[BLD]>(psm + NB * BLD);
+  float (*Tmp)[BLD] = reinterpret_cast<float (*)[BLD]>(psm + 2 * NB * BLD);
+  float (*Po)[BLD] = reinterpret_cast<float (*)[BLD]>(psm + 3 * NB * BLD);
+  float (*Pd)[PLD] = reinterpret_cast<float (*)[PLD]>(psm + 4 * NB * BLD);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lm = lane & 15, lk = lane >> 4;
+  const int Kp = (int)(c0 - J);               // columns of this panel already factored: 0, 64, 128, 192
+
+  // raw diagonal block (identity beyond nb, strict upper part zero) and the diagonal rows'
+  // earlier columns of L; all loads are issued before the first use
+  {
+    float ld[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int e = tid + 256 * u, rr = e >> 6, cc = e & 63;
+      const bool in = rr < nb && cc <= rr;
+      const float v = W[(c0 + (in ? rr : 0)) * n + c0 + (in ? cc : 0)];
+      ld[u] = in ? v : ((rr == cc) ? 1.f : 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int e = tid + 256 * u;
+      M[e >> 6][e & 63] = ld[u];
+    }
+  }
+  for (int kc = 0; kc < Kp; kc += NB) {
+    float ld[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int e = tid + 256 * u, rr = e >> 6, cc = e & 63;
+      const float v = L[(c0 + (rr < nb ? rr : 0)) * ldl + J + kc + cc];
+      ld[u] = rr < nb ? v : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int e = tid + 256 * u;
+      Pd[e >> 6][kc + (e & 63)] = ld[u];
+    }
   }
   __syncthreads();
-  float a[16];
+  // diagonal block -= (earlier columns) (earlier columns)^T; a wavefront touches its 16 rows only
+  if (Kp > 0) {
+    floatx4 acc[4];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) a[i] = Lout[r][g + 4 * i];
-  __syncthreads();
-  for (int ik = 0; ik < 16; ++ik) {
-    potf_step<0>(a, ik, r, g, nb, k0, info, vbuf, piv, Lout);
-    potf_step<1>(a, ik, r, g, nb, k0, info, vbuf, piv, Lout);
-    potf_step<2>(a, ik, r, g, nb, k0, info, vbuf, piv, Lout);
-    potf_step<3>(a, ik, r, g, nb, k0, info, vbuf, piv, Lout);
-    const float t0 = a[0];
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int i = 0; i < 15; ++i) a[i] = a[i + 1];
-    a[15] = t0;
+      for (int r = 0; r < 4; ++r) acc[t][r] = M[16 * wave + 4 * lk + r][16 * t + lm];
+    strip_mma(acc, &Pd[0][0], PLD, &Pd[0][0], PLD, Kp, wave, lm, lk, -1.f);
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) M[16 * wave + 4 * lk + r][16 * t + lm] = acc[t][r];
   }
   __syncthreads();
-  for (int e = tid; e < NB * NB; e += 256) {
-    const int rr = e >> 6, cc = e & 63;
-    if (rr < nb && cc <= rr) L[(k0 + rr) * ldl + k0 + cc] = Lout[rr][cc];
+  factor_block(M, Inv, Tmp, nb, c0, info);
+  if (blockIdx.x == 0) {
+    for (int e = tid; e < NB * NB; e += 256) {
+      const int rr = e >> 6, cc = e & 63;
+      if (rr < nb && cc <= rr) L[(c0 + rr) * ldl + c0 + cc] = M[rr][cc];
+    }
   }
+  const int64_t r0 = c0 + NB + (int64_t)blockIdx.x * NB;
+  if (r0 >= n) return;
+  // own rows: X = W[rows, block] - L[rows, earlier columns] (diagonal rows' earlier columns)^T
+  floatx4 acc[4];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int c = g + 4 * i;
-    inv[r * NB + c] = (c <= r) ? a[i] : 0.f;
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int64_t row = r0 + 16 * wave + 4 * lk + r;
+      const int col = 16 * t + lm;
+      acc[t][r] = (row < n && col < nb) ? W[row * n + c0 + col] : 0.f;
+    }
+  for (int kc = 0; kc < Kp; kc += NB) {
+    float ld[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int e = tid + 256 * u, rr = e >> 6, cc = e & 63;
+      const bool in = r0 + rr < n;
+      const float v = L[(r0 + (in ? rr : 0)) * ldl + J + kc + cc];
+      ld[u] = in ? v : 0.f;
+    }
+    __syncthreads();                    // the previous chunk has been consumed
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int e = tid + 256 * u;
+      Po[e >> 6][e & 63] = ld[u];
+    }
+    __syncthreads();
+    strip_mma(acc, &Po[0][0], BLD, &Pd[0][kc], PLD, NB, wave, lm, lk, -1.f);
   }
+  // rows = X inv(factor)^T; X goes through LDS to become the left operand (each wavefront
+  // reads back only the 16 rows it wrote)
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) Tmp[16 * wave + 4 * lk + r][16 * t + lm] = acc[t][r];
+  floatx4 out[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) out[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+  strip_mma(out, &Tmp[0][0], BLD, &Inv[0][0], BLD, NB, wave, lm, lk, 1.f);
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int64_t row = r0 + 16 * wave + 4 * lk + r;
+      const int col = 16 * t + lm;
+      if (row < n && col < nb) L[row * ldl + c0 + col] = out[t][r];
+    }
 }
 
 }  // namespace
 
+constexpr int kOuter = 4 * NB;
+constexpr int kPanelLds = (4 * NB * BLD + NB * PLD) * (int)sizeof(float);
+
 size_t cholesky_scratch_bytes(int64_t n) {
-  return kAlign + align_up((size_t)n * sizeof(float)) + align_up((size_t)NB * NB * sizeof(float));
+  return kAlign + align_up((size_t)n * sizeof(float)) + align_up((size_t)n * n * sizeof(float));
 }
 
 hipError_t launch_cholesky(hipStream_t s, const float* H, int64_t n, int64_t ldh, int precond,
                            float lambda, float* L, int64_t ldl, int* info_dev) {
-  // info_dev points at scratch: [int info][pad to 256][float delta[n]][float inv[64 x 64]]
+  // info_dev points at scratch: [int info][pad to 256][float delta[n]][float W[n x n]]
   float* delta = reinterpret_cast<float*>(reinterpret_cast<char*>(info_dev) + kAlign);
-  float* inv = reinterpret_cast<float*>(reinterpret_cast<char*>(delta) + align_up((size_t)n * sizeof(float)));
+  float* W = reinterpret_cast<float*>(reinterpret_cast<char*>(delta) + align_up((size_t)n * sizeof(float)));
   hipError_t e;
+  static bool attr_set = false;
+  if (!attr_set) {
+    e = hipFuncSetAttribute((const void*)chol_panel_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kPanelLds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
   hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(1), 0, s, info_dev, 0);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (precond == GANQ_PRECOND_DIAGDOM) {
@@ -178,23 +411,23 @@ hipError_t launch_cholesky(hipStream_t s, const float* H, int64_t n, int64_t ldh
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   hipLaunchKernelGGL(copy_lower_kernel, dim3((unsigned)ceil_div(n, 256), (unsigned)n), dim3(256),
-                     0, s, H, n, ldh, L, ldl, precond, lambda, delta);
+                     0, s, H, n, ldh, W, L, ldl, precond, lambda, delta);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  for (int64_t k0 = 0; k0 < n; k0 += NB) {
-    const int nb = (int)((n - k0 < NB) ? n - k0 : NB);
-    hipLaunchKernelGGL(potf2_inv_kernel, dim3(1), dim3(256), 0, s, L, ldl, k0, nb, info_dev, inv);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    const int64_t rem = n - k0 - nb;
+  for (int64_t J = 0; J < n; J += kOuter) {
+    for (int64_t c0 = J; c0 < n && c0 < J + kOuter; c0 += NB) {
+      const int nb = (int)((n - c0 < NB) ? n - c0 : NB);
+      const int64_t rem = n - c0 - NB;
+      const unsigned wgs = rem > 0 ? (unsigned)ceil_div(rem, NB) : 1u;
+      hipLaunchKernelGGL(chol_panel_kernel, dim3(wgs), dim3(256), kPanelLds, s, W, L, ldl, n, J, c0, nb,
+                         info_dev);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    const int64_t rem = n - J - kOuter;
     if (rem <= 0) break;
-    float* A21 = L + (k0 + nb) * ldl + k0;
-    float* A22 = L + (k0 + nb) * ldl + (k0 + nb);
-    // panel solve as a product with the inverse of the diagonal factor, in place: each
-    // workgroup of the GEMM reads all of its rows of A21 before it writes them
-    e = launch_gemm_f32(s, /*transb=*/1, /*lower_only=*/0, rem, nb, nb, 1.f, A21, ldl, inv, NB, 0.f,
-                        A21, ldl);
-    if (e != hipSuccess) return e;
-    e = launch_gemm_f32(s, /*transb=*/1, /*lower_only=*/1, rem, rem, nb, -1.f, A21, ldl, A21, ldl,
-                        1.f, A22, ldl);
+    // W22 -= L21 L21^T, lower tiles only
+    const float* L21 = L + (J + kOuter) * ldl + J;
+    e = launch_gemm_f32(s, /*transb=*/1, /*lower_only=*/1, rem, rem, kOuter, -1.f, L21, ldl, L21, ldl, 1.f,
+                        W + (J + kOuter) * n + (J + kOuter), n);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
