@@ -108,6 +108,16 @@ const char* ganq_last_error(const ganq_ctx* ctx);
 ganq_status ganq_build_hessian(ganq_ctx* ctx, const void* X, ganq_dtype x_dtype, int64_t n,
                                int64_t p, int64_t ldx, float* H, int64_t ldh, int accumulate);
 
+/* The same H = X X^T for activations stored the way calibration batches arrive
+ * (Section 4.1 Setup: sequences of tokens through the layer): Xt is p x n
+ * (tokens x features) row-major with leading dimension ldxt >= n, so
+ * H = Xt^T Xt.  Any p >= 0 and any ldxt >= n.  The chunk is transposed into
+ * workspace (at most 32768 tokens at a time, zero-padded to a multiple of 8)
+ * and then takes the path of ganq_build_hessian; accumulate as there. */
+ganq_status ganq_build_hessian_tokens(ganq_ctx* ctx, const void* Xt, ganq_dtype x_dtype, int64_t n,
+                                      int64_t p, int64_t ldxt, float* H, int64_t ldh,
+                                      int accumulate);
+
 /* L = lower Cholesky factor of H (or of its preconditioned form), Eq. (10),
  * Remark 3.1, Appendix A.  L is n x n fp32 with the strict upper triangle
  * zeroed; L may not alias H.  *info_host: 0 on success, k > 0 if pivot k

@@ -22,7 +22,8 @@ INIT_QUANTILE_MID, INIT_QUANTILE_ENDPOINTS, INIT_MINMAX_GRID = range(3)
 EMPTY_ZERO, EMPTY_KEEP = 0, 1
 
 EXPORTS = ["ganq_create", "ganq_destroy", "ganq_workspace_bytes", "ganq_set_workspace",
-           "ganq_status_string", "ganq_last_error", "ganq_build_hessian", "ganq_cholesky",
+           "ganq_status_string", "ganq_last_error", "ganq_build_hessian", "ganq_build_hessian_tokens",
+           "ganq_cholesky",
            "ganq_init_codebooks", "ganq_update_S", "ganq_update_T", "ganq_layer_loss",
            "ganq_quantize_layer", "ganq_profile_enable", "ganq_profile_read"]
 
@@ -67,6 +68,8 @@ def load_library():
     lib.ganq_last_error.restype = ctypes.c_char_p
     lib.ganq_build_hessian.argtypes = [vp, vp, ci, i64, i64, i64, vp, i64, ci]
     lib.ganq_build_hessian.restype = ci
+    lib.ganq_build_hessian_tokens.argtypes = [vp, vp, ci, i64, i64, i64, vp, i64, ci]
+    lib.ganq_build_hessian_tokens.restype = ci
     lib.ganq_cholesky.argtypes = [vp, vp, i64, i64, ci, cf, vp, i64, ctypes.POINTER(i64)]
     lib.ganq_cholesky.restype = ci
     lib.ganq_init_codebooks.argtypes = [vp, vp, ci, i64, i64, i64, ci, ci, vp]
@@ -173,6 +176,16 @@ class Context:
         self.reserve(0, n, p, 4)
         self._check(self.lib.ganq_build_hessian(self.handle, _ptr(X), _dtype_code(X), n, p, ldx,
                                                 _ptr(H), _rowmajor(H, "H"), int(accumulate)))
+        return H
+
+    def build_hessian_tokens(self, Xt, H=None, accumulate=False):
+        p, n = Xt.shape
+        ldxt = _rowmajor(Xt, "Xt")
+        if H is None:
+            H = torch.empty(n, n, dtype=torch.float32, device=Xt.device)
+        self.reserve(0, n, p, 4)
+        self._check(self.lib.ganq_build_hessian_tokens(self.handle, _ptr(Xt), _dtype_code(Xt), n, p, ldxt,
+                                                       _ptr(H), _rowmajor(H, "H"), int(accumulate)))
         return H
 
     def cholesky(self, H, precond=PRECOND_NONE, lam=0.0, L=None, raise_on_fail=True):

@@ -178,6 +178,13 @@ size_t ganq_workspace_bytes(int64_t m, int64_t n, int64_t p_tokens, int nbits) {
   size_t h = hessian_scratch_bytes(n, p_tokens > 0 ? p_tokens : 1) + kAlign;
   size_t h32 = align_up((size_t)n * n * sizeof(float)) + kAlign;
   if (h32 > h) h = h32;
+  if (p_tokens > 0) {     // token-major entry point: transposed chunk + the scratch of its product
+    const int64_t pc = p_tokens < kTokenChunk ? (p_tokens + 7) / 8 * 8 : kTokenChunk;
+    size_t hp = hessian_scratch_bytes(n, pc) + kAlign;
+    if (h32 > hp) hp = h32;
+    const size_t ht = align_up((size_t)n * pc * sizeof(float)) + hp + kAlign;
+    if (ht > h) h = ht;
+  }
   return q > h ? q : h;
 }
 
@@ -266,6 +273,45 @@ ganq_status ganq_build_hessian(ganq_ctx* ctx, const void* X, ganq_dtype x_dtype,
     GANQ_HIP(ctx, launch_gemm_f32(s, 1, 1, n, n, p, 1.f, (const float*)X, ldx, (const float*)X, ldx,
                                   0.f, tmp, n));
     GANQ_HIP(ctx, launch_mirror_lower(s, H, n, ldh, tmp, n, accumulate));
+  }
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
+ganq_status ganq_build_hessian_tokens(ganq_ctx* ctx, const void* Xt, ganq_dtype x_dtype, int64_t n,
+                                      int64_t p, int64_t ldxt, float* H, int64_t ldh,
+                                      int accumulate) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  GANQ_REQUIRE(ctx, dtype_ok(x_dtype), "x_dtype");
+  GANQ_REQUIRE(ctx, n > 0 && p >= 0, "n must be positive and p non-negative");
+  GANQ_REQUIRE(ctx, H != nullptr && ldh >= n, "H / ldh");
+  GANQ_REQUIRE(ctx, p == 0 || (Xt != nullptr && ldxt >= n), "Xt / ldxt");
+  if (p == 0) return ganq_build_hessian(ctx, nullptr, x_dtype, n, 0, 0, H, ldh, accumulate);
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  hipStream_t s = ctx->stream;
+  const int eb = (x_dtype == GANQ_F16) ? 2 : 4;
+  const int64_t pcmax = p < kTokenChunk ? (p + 7) / 8 * 8 : kTokenChunk;
+  Arena ar(ctx->ws, ctx->ws_bytes);
+  void* Xn = ar.take((size_t)n * pcmax * eb);
+  float* part = (float*)ar.take(x_dtype == GANQ_F16 ? hessian_scratch_bytes(n, pcmax)
+                                                    : (size_t)n * n * sizeof(float));
+  if (Xn == nullptr || part == nullptr)
+    return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for H = Xt^T Xt");
+  ProfScope prof(ctx, GANQ_K_HESSIAN);
+  for (int64_t k0 = 0; k0 < p; k0 += kTokenChunk) {
+    const int64_t pc = (p - k0 < kTokenChunk) ? p - k0 : kTokenChunk;
+    const int64_t pc8 = (pc + 7) / 8 * 8;                 // zero-padded tokens add nothing to H
+    const char* src = (const char*)Xt + (size_t)k0 * ldxt * eb;
+    GANQ_HIP(ctx, launch_transpose_tokens(s, src, eb, pc, n, ldxt, Xn, pc8));
+    const int acc = (accumulate != 0 || k0 > 0) ? 1 : 0;
+    if (x_dtype == GANQ_F16) {
+      GANQ_HIP(ctx, launch_hessian_f16(s, (const _Float16*)Xn, n, pc8, pc8, H, ldh, acc, part));
+    } else {
+      GANQ_HIP(ctx, launch_gemm_f32(s, 1, 1, n, n, pc8, 1.f, (const float*)Xn, pc8, (const float*)Xn, pc8,
+                                    0.f, part, n));
+      GANQ_HIP(ctx, launch_mirror_lower(s, H, n, ldh, part, n, acc));
+    }
   }
   ctx->last_error.clear();
   return GANQ_OK;

@@ -59,6 +59,9 @@ constexpr int kHessMaxSplit = 16;   // upper bound on token-axis splits
 inline int64_t pad_rows(int64_t m) { return ceil_div(m, kSlabRows) * kSlabRows; }
 int hessian_split(int64_t n, int64_t p);
 size_t hessian_scratch_bytes(int64_t n, int64_t p);
+constexpr int64_t kTokenChunk = 32768;   // tokens transposed at a time by the token-major entry point
+hipError_t launch_transpose_tokens(hipStream_t s, const void* Xt, int elem_bytes, int64_t pc, int64_t n,
+                                   int64_t ldxt, void* Xn, int64_t ldn);
 size_t update_s_scratch_bytes(int64_t m, int64_t n);
 size_t update_t_scratch_bytes(int64_t m, int64_t n, int nbits);
 size_t loss_scratch_bytes(int64_t m, int64_t n);

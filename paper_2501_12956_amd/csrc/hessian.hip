@@ -205,6 +205,25 @@ __global__ __launch_bounds__(256) void reduce_mirror_kernel(float* __restrict__ 
   }
 }
 
+// Xn[f][k] = Xt[k][f] for k < pc, 0 for pc <= k < ldn: tokens x features -> features x tokens
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_tokens_kernel(const T* __restrict__ Xt, int64_t pc,
+                                                               int64_t n, int64_t ldxt,
+                                                               T* __restrict__ Xn, int64_t ldn) {
+  __shared__ T tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 x 8
+  const int64_t k0 = (int64_t)blockIdx.x * 32, f0 = (int64_t)blockIdx.y * 32;
+  for (int r = ty; r < 32; r += 8) {
+    const int64_t k = k0 + r, f = f0 + tx;
+    tile[r][tx] = (k < pc && f < n) ? Xt[k * ldxt + f] : (T)0;
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) {
+    const int64_t f = f0 + r, k = k0 + tx;
+    if (f < n && k < ldn) Xn[f * ldn + k] = tile[tx][r];
+  }
+}
+
 }  // namespace
 
 int hessian_split(int64_t n, int64_t p) {
@@ -243,6 +262,18 @@ hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64
   dim3 g2((unsigned)ceil_div(n, 32), (unsigned)ceil_div(n, 32));
   hipLaunchKernelGGL(reduce_mirror_kernel, g2, dim3(256), 0, s, H, n, ldh, partials, n, split,
                      accumulate);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose_tokens(hipStream_t s, const void* Xt, int elem_bytes, int64_t pc, int64_t n,
+                                   int64_t ldxt, void* Xn, int64_t ldn) {
+  dim3 grid((unsigned)ceil_div(ldn, 32), (unsigned)ceil_div(n, 32));
+  if (elem_bytes == 2)
+    hipLaunchKernelGGL(transpose_tokens_kernel<_Float16>, grid, dim3(256), 0, s, (const _Float16*)Xt, pc, n,
+                       ldxt, (_Float16*)Xn, ldn);
+  else
+    hipLaunchKernelGGL(transpose_tokens_kernel<float>, grid, dim3(256), 0, s, (const float*)Xt, pc, n, ldxt,
+                       (float*)Xn, ldn);
   return hipGetLastError();
 }
 

@@ -103,8 +103,33 @@ def test_hessian_fp32_and_strided(ctx):
     assert np.array_equal(Hv, H.astype(np.float32))
 
 
+@pytest.mark.parametrize("n,p,dtype", [(300, 1093, torch.float16), (130, 5, torch.float16),
+                                       (200, 515, torch.float32)])
+def test_hessian_token_major(ctx, n, p, dtype):
+    """Activations stored tokens x features (how calibration batches arrive): H = Xt^T Xt, any
+    token count, chunks accumulated; the oracle is the same float64 X X^T."""
+    g = torch.Generator().manual_seed(21)
+    Xt = torch.randn(p, n, generator=g).to(dtype)
+    Xt[:, 3] *= 20.0
+    Href = ref.build_hessian(Xt.numpy().astype(np.float64).T)
+    Xg = Xt.cuda()
+    H = ctx.build_hessian_tokens(Xg).cpu().numpy().astype(np.float64)
+    check_H(H, Href, p, "token-major %s n=%d p=%d" % (str(dtype), n, p))
+    assert np.array_equal(H, H.T)
+    if p >= 16:
+        cut = p // 3
+        H2 = ctx.build_hessian_tokens(Xg[:cut])
+        H2 = ctx.build_hessian_tokens(Xg[cut:], H=H2, accumulate=True).cpu().numpy().astype(np.float64)
+        check_H(H2, Href, p, "token-major two chunks")
+        # a strided view (leading dimension larger than n)
+        big = torch.zeros(p, n + 24, dtype=dtype, device="cuda")
+        big[:, :n] = Xg
+        Hv = ctx.build_hessian_tokens(big[:, :n]).cpu().numpy().astype(np.float64)
+        assert np.array_equal(Hv, H)
+
+
 # ----------------------------------------------------------------------------- L
-@pytest.mark.parametrize("n", [200, 64, 65, 1])
+@pytest.mark.parametrize("n", [200, 64, 65, 1, 300, 523])
 def test_cholesky(ctx, n):
     _, X = make_problem(4, n, max(4 * n, 64), 4, x_dtype=torch.float32, w_kind="gauss_outlier")
     H32 = (X @ X.T).contiguous()
@@ -314,3 +339,50 @@ def test_quantize_layer_fp16_weights_and_init_inside(ctx):
     T0 = ctx.init_codebooks(W16.cuda(), nbits)
     T1, Q1 = ctx.quantize_layer(Wf, H, nbits, 3, T=T0.clone())
     assert torch.equal(T, T1) and torch.equal(Q, Q1)
+
+
+@pytest.mark.parametrize("mode", ["lambda", "diagdom", "auto"])
+def test_quantize_layer_rank_deficient_activations(ctx, mode):
+    """Fewer calibration tokens than input features (p < n): H = X X^T is singular and the
+    plain factorization fails (Remark 3.1, Appendix A).  The preconditioned factor drives the
+    S-update; the T-update and the objective keep the raw H.  Stage-wise against the oracle."""
+    from paper_2501_12956_amd import binding as b
+    m, n, p, nbits, K = 40, 320, 160, 4, 4
+    g = torch.Generator().manual_seed(5)
+    W = (torch.randn(m, n, generator=g) * 0.02).float()
+    Xt = torch.randn(p, n, generator=g).float()          # tokens x features
+    Xt[:, 7] *= 20.0
+    Wg = W.cuda()
+    H = ctx.build_hessian_tokens(Xt.cuda())
+    with pytest.raises(b.GanqError) as exc:
+        ctx.quantize_layer(Wg, H, nbits, 1, precond=b.PRECOND_NONE)
+    assert exc.value.status == b.GANQ_ERR_NOT_PD
+    gmode = {"lambda": b.PRECOND_LAMBDA, "diagdom": b.PRECOND_DIAGDOM, "auto": b.PRECOND_AUTO}[mode]
+    omode = {"lambda": ref.PRECOND_LAMBDA, "diagdom": ref.PRECOND_DIAGDOM, "auto": ref.PRECOND_DIAGDOM}[mode]
+    H64 = H.cpu().numpy().astype(np.float64)
+    lam = 1e-2 * float(np.mean(np.diag(H64))) if mode == "lambda" else 0.0
+    T, Q, hist = ctx.quantize_layer(Wg, H, nbits, K, precond=gmode, lam=lam, history=True)
+    Tprev, _ = ctx.quantize_layer(Wg, H, nbits, K - 1, precond=gmode, lam=lam)
+    W64 = W.numpy().astype(np.float64)
+    # the oracle's factor of the preconditioned matrix; the GPU's own factor is checked against it
+    Lref, _ = ref.cholesky(H64, omode, lam)
+    Lg, info = ctx.cholesky(H, gmode, lam)
+    assert info == 0
+    assert np.linalg.norm(Lg.cpu().numpy() - Lref) <= 1e-3 * np.linalg.norm(Lref)
+    L64 = Lg.cpu().numpy().astype(np.float64)
+    _, _, viol = check_S(W64, L64, Tprev.cpu().numpy().astype(np.float64), Q.cpu().numpy(), "rank-deficient " + mode)
+    assert viol == 0
+    Tref, _ = ref.update_T(W64, H64, Q.cpu().numpy(), nbits)        # raw H
+    err = np.abs(T.cpu().numpy() - Tref).max(axis=1) / np.abs(Tref).max(axis=1)
+    print("rank-deficient %s: T-update max row error %.2e" % (mode, err.max()))
+    assert np.all(err <= 1e-4)
+    lref = ref.layer_loss(W64, H64, T.cpu().numpy(), Q.cpu().numpy())[0]
+    assert abs(hist[-1] - lref) <= 1e-4 * lref
+    for k in range(K):
+        assert hist[2 * k + 1] <= hist[2 * k] * (1 + 1e-5)
+    # it beats rounding every weight onto T^0 in the same objective
+    T0 = ref.init_codebooks(W64, nbits)
+    Q0 = np.abs(W64[:, :, None] - T0[:, None, :]).argmin(axis=2)
+    l0 = ref.layer_loss(W64, H64, T0, Q0)[0]
+    print("rank-deficient %s: loss %.4e vs nearest rounding onto T0 %.4e" % (mode, hist[-1], l0))
+    assert hist[-1] < l0
