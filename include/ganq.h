@@ -174,6 +174,25 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
                                 const ganq_options* opts, float* T, uint8_t* Q, int64_t ldq,
                                 double* loss_history_host);
 
+/* ---- optional pre-step ------------------------------------------------------ */
+
+/* Outlier split W = W_sparse + W_dense (Appendix B, Algorithm 2; Section 3.3).
+ * With p = 1 - r/2, per row the cut-offs are the values at sorted positions
+ * lower = ceil(n (1 - p)) and upper = min(floor(n p), n - 1) (positions computed
+ * in double exactly as written); entries >= the upper or <= the lower cut-off
+ * are outliers.  W is m x n fp16 or fp32; W_dense is m x n fp32 with zeros at
+ * the outlier positions and feeds ganq_quantize_layer unchanged.  W_sparse is
+ * returned as CSR: row_ptr (m + 1 entries, int64), col_idx and values (columns
+ * ascending within a row; values are the stored weights, exact).  capacity =
+ * entries that col_idx / values can hold; *nnz_host receives the number of
+ * outliers.  If it exceeds capacity the status is GANQ_ERR_INVALID_ARG,
+ * W_dense and row_ptr are complete and the first `capacity` entries were
+ * written: call again with larger arrays.  0 <= r < 1; n <= 32768.
+ * Synchronises. */
+ganq_status ganq_outlier_split(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype, int64_t m, int64_t n,
+                               int64_t ldw, double r, float* W_dense, int64_t ldd, int64_t* row_ptr,
+                               int32_t* col_idx, float* values, int64_t capacity, int64_t* nnz_host);
+
 /* ---- optional per-kernel timing (measurement aid, not part of the method) ------ */
 
 /* Kernel classes the library launches; one step of Algorithm 1 touches all of them. */
@@ -188,7 +207,8 @@ typedef enum {
   GANQ_K_T_ACCUM = 7,  /* one-hot GEMM of the T-update, once per sweep */
   GANQ_K_T_SOLVE = 8,  /* per-row assembly and solve, once per sweep */
   GANQ_K_LOSS = 9,     /* objective evaluation */
-  GANQ_K_COUNT = 10
+  GANQ_K_OUTLIER = 10, /* outlier split (sort, offsets, compaction) */
+  GANQ_K_COUNT = 11
 } ganq_kernel_class;
 
 /* on != 0: bracket every kernel class launched through this context with HIP

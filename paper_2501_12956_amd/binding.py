@@ -25,10 +25,10 @@ EXPORTS = ["ganq_create", "ganq_destroy", "ganq_workspace_bytes", "ganq_set_work
            "ganq_status_string", "ganq_last_error", "ganq_build_hessian", "ganq_build_hessian_tokens",
            "ganq_cholesky",
            "ganq_init_codebooks", "ganq_update_S", "ganq_update_T", "ganq_layer_loss",
-           "ganq_quantize_layer", "ganq_profile_enable", "ganq_profile_read"]
+           "ganq_quantize_layer", "ganq_outlier_split", "ganq_profile_enable", "ganq_profile_read"]
 
 KERNEL_CLASSES = ["hessian", "cholesky", "init", "gemm_wh", "update_s", "t_prep", "t_pad", "t_accum",
-                  "t_solve", "loss"]
+                  "t_solve", "loss", "outlier"]
 
 
 class GanqOptions(ctypes.Structure):
@@ -85,6 +85,9 @@ def load_library():
                                         ctypes.POINTER(GanqOptions), vp, vp, i64,
                                         ctypes.POINTER(ctypes.c_double)]
     lib.ganq_quantize_layer.restype = ci
+    lib.ganq_outlier_split.argtypes = [vp, vp, ci, i64, i64, i64, ctypes.c_double, vp, i64, vp, vp, vp, i64,
+                                       ctypes.POINTER(i64)]
+    lib.ganq_outlier_split.restype = ci
     lib.ganq_profile_enable.argtypes = [vp, ci]
     lib.ganq_profile_enable.restype = ci
     lib.ganq_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -145,10 +148,11 @@ class Context:
             raise GanqError(st, self.lib.ganq_last_error(self.handle).decode() or
                             self.lib.ganq_status_string(st).decode())
 
-    def reserve(self, m, n, p=0, nbits=4):
+    def reserve(self, m, n, p=0, nbits=4, extra=0):
         need = self.lib.ganq_workspace_bytes(m, n, p, nbits)
         if need == 0:
             raise ValueError("invalid shape for workspace query")
+        need += extra
         if self._ws is None or self._ws.numel() < need:
             self._ws = None
             self._ws = torch.empty(need, dtype=torch.uint8, device=self.device)
@@ -183,7 +187,8 @@ class Context:
         ldxt = _rowmajor(Xt, "Xt")
         if H is None:
             H = torch.empty(n, n, dtype=torch.float32, device=Xt.device)
-        self.reserve(0, n, p, 4)
+        # room to transpose all tokens at once (the library takes what the workspace holds)
+        self.reserve(0, n, p, 4, extra=min(n * (p + 8) * Xt.element_size(), 8 << 30))
         self._check(self.lib.ganq_build_hessian_tokens(self.handle, _ptr(Xt), _dtype_code(Xt), n, p, ldxt,
                                                        _ptr(H), _rowmajor(H, "H"), int(accumulate)))
         return H
@@ -238,6 +243,30 @@ class Context:
                                              _rowmajor(H, "H"), _ptr(T), _ptr(Q), _rowmajor(Q, "Q"),
                                              nbits, ctypes.byref(out), _ptr(rows)))
         return (out.value, rows) if want_rows else out.value
+
+    def outlier_split(self, W, r, capacity=None):
+        """(W_dense fp32, row_ptr int64, col_idx int32, values fp32) of Algorithm 2; the CSR
+        arrays are trimmed to the number of outliers."""
+        m, n = W.shape
+        dev = W.device
+        Wd = torch.empty(m, n, dtype=torch.float32, device=dev)
+        row_ptr = torch.empty(m + 1, dtype=torch.int64, device=dev)
+        self.reserve(m, n, 0, 4)
+        if capacity is None:
+            capacity = m * (2 * (int(n * r * 0.5) + 2) + 8)
+        nnz = ctypes.c_int64(0)
+        for _ in range(2):
+            col = torch.empty(max(capacity, 1), dtype=torch.int32, device=dev)
+            val = torch.empty(max(capacity, 1), dtype=torch.float32, device=dev)
+            st = self.lib.ganq_outlier_split(self.handle, _ptr(W), _dtype_code(W), m, n, _rowmajor(W, "W"),
+                                             float(r), _ptr(Wd), n, _ptr(row_ptr), _ptr(col), _ptr(val),
+                                             capacity, ctypes.byref(nnz))
+            if st == GANQ_ERR_INVALID_ARG and nnz.value > capacity:
+                capacity = nnz.value          # ties at a cut-off: size the arrays exactly and repeat
+                continue
+            break
+        self._check(st)
+        return Wd, row_ptr, col[:nnz.value], val[:nnz.value]
 
     def quantize_layer(self, W, H, nbits, iters, T=None, L=None, precond=PRECOND_NONE, lam=0.0,
                        init=INIT_QUANTILE_MID, empty=EMPTY_ZERO, Q=None, history=False):

@@ -94,6 +94,7 @@ size_t quantize_scratch_bytes(int64_t m, int64_t n, int nbits) {
   b += update_s_scratch_bytes(m, n);
   b += update_t_scratch_bytes(m, n, nbits);
   b += loss_scratch_bytes(m, n);
+  b += outlier_scratch_bytes(m);
   return b + 8 * kAlign;
 }
 
@@ -179,10 +180,11 @@ size_t ganq_workspace_bytes(int64_t m, int64_t n, int64_t p_tokens, int nbits) {
   size_t h32 = align_up((size_t)n * n * sizeof(float)) + kAlign;
   if (h32 > h) h = h32;
   if (p_tokens > 0) {     // token-major entry point: transposed chunk + the scratch of its product
-    const int64_t pc = p_tokens < kTokenChunk ? (p_tokens + 7) / 8 * 8 : kTokenChunk;
-    size_t hp = hessian_scratch_bytes(n, pc) + kAlign;
+    const int64_t p8 = (p_tokens + 7) / 8 * 8;
+    const int64_t pc = p8 < kTokenChunk ? p8 : kTokenChunk;
+    size_t hp = hessian_scratch_bytes(n, p8) + kAlign;
     if (h32 > hp) hp = h32;
-    const size_t ht = align_up((size_t)n * pc * sizeof(float)) + hp + kAlign;
+    const size_t ht = align_up((size_t)n * pc * sizeof(float)) + hp + 4 * kAlign;
     if (ht > h) h = ht;
   }
   return q > h ? q : h;
@@ -194,6 +196,51 @@ ganq_status ganq_set_workspace(ganq_ctx* ctx, void* dev_ptr, size_t bytes) {
   GANQ_REQUIRE(ctx, ((uintptr_t)dev_ptr) % kAlign == 0, "workspace must be 256-byte aligned");
   ctx->ws = dev_ptr;
   ctx->ws_bytes = bytes;
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
+ganq_status ganq_outlier_split(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype, int64_t m, int64_t n,
+                               int64_t ldw, double r, float* W_dense, int64_t ldd, int64_t* row_ptr,
+                               int32_t* col_idx, float* values, int64_t capacity, int64_t* nnz_host) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  if (nnz_host != nullptr) *nnz_host = 0;
+  GANQ_REQUIRE(ctx, dtype_ok(w_dtype), "w_dtype");
+  GANQ_REQUIRE(ctx, m > 0 && n > 0, "m and n must be positive");
+  GANQ_REQUIRE(ctx, W != nullptr && ldw >= n, "W / ldw");
+  GANQ_REQUIRE(ctx, W_dense != nullptr && ldd >= n, "W_dense / ldd");
+  GANQ_REQUIRE(ctx, row_ptr != nullptr && nnz_host != nullptr, "row_ptr / nnz_host");
+  GANQ_REQUIRE(ctx, capacity >= 0 && (capacity == 0 || (col_idx != nullptr && values != nullptr)),
+               "col_idx / values / capacity");
+  GANQ_REQUIRE(ctx, r >= 0.0 && r < 1.0, "r must be in [0, 1)");
+  if (n > 32768) return fail(ctx, GANQ_ERR_UNSUPPORTED, "outlier split sorts a row in LDS: n <= 32768");
+  // sorted positions of the two cut-offs, in double exactly as the definition writes them
+  const double p = 1.0 - 0.5 * r;
+  int64_t upper = (int64_t)floor((double)n * p);
+  if (upper > n - 1) upper = n - 1;
+  const int64_t lower = (int64_t)ceil((double)n * (1.0 - p));
+  GANQ_REQUIRE(ctx, lower >= 0 && lower <= n - 1, "r too large for this n");
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  hipStream_t s = ctx->stream;
+  Arena ar(ctx->ws, ctx->ws_bytes);
+  void* scratch = ar.take(outlier_scratch_bytes(m));
+  if (scratch == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the outlier split");
+  {
+    ProfScope prof(ctx, GANQ_K_OUTLIER);
+    GANQ_HIP(ctx, launch_outlier_split(s, W, w_dtype == GANQ_F16, m, n, ldw, (int)lower, (int)upper, W_dense,
+                                       ldd, row_ptr, col_idx, values, capacity, scratch));
+  }
+  int64_t nnz = 0;
+  GANQ_HIP(ctx, hipMemcpyAsync(&nnz, row_ptr + m, sizeof(int64_t), hipMemcpyDeviceToHost, s));
+  GANQ_HIP(ctx, hipStreamSynchronize(s));
+  *nnz_host = nnz;
+  if (nnz > capacity) {
+    char buf[128];
+    snprintf(buf, sizeof buf, "%lld outliers do not fit a capacity of %lld", (long long)nnz,
+             (long long)capacity);
+    return fail(ctx, GANQ_ERR_INVALID_ARG, buf);
+  }
   ctx->last_error.clear();
   return GANQ_OK;
 }
@@ -291,16 +338,24 @@ ganq_status ganq_build_hessian_tokens(ganq_ctx* ctx, const void* Xt, ganq_dtype 
   if (st != GANQ_OK) return st;
   hipStream_t s = ctx->stream;
   const int eb = (x_dtype == GANQ_F16) ? 2 : 4;
-  const int64_t pcmax = p < kTokenChunk ? (p + 7) / 8 * 8 : kTokenChunk;
+  // Tokens per transposed chunk: what the workspace holds beyond the scratch of the product
+  // (at least kTokenChunk, which ganq_workspace_bytes guarantees; a larger workspace means
+  // fewer, larger products).
+  const int64_t p8 = (p + 7) / 8 * 8;
+  const size_t part_bytes = (x_dtype == GANQ_F16) ? hessian_scratch_bytes(n, p8) : (size_t)n * n * sizeof(float);
+  int64_t chunk = p8 < kTokenChunk ? p8 : kTokenChunk;
+  if (ctx->ws_bytes > part_bytes + 4 * kAlign) {
+    const int64_t fit = (int64_t)((ctx->ws_bytes - part_bytes - 4 * kAlign) / ((size_t)n * eb)) / 2048 * 2048;
+    if (fit > chunk) chunk = fit < p8 ? fit : p8;
+  }
   Arena ar(ctx->ws, ctx->ws_bytes);
-  void* Xn = ar.take((size_t)n * pcmax * eb);
-  float* part = (float*)ar.take(x_dtype == GANQ_F16 ? hessian_scratch_bytes(n, pcmax)
-                                                    : (size_t)n * n * sizeof(float));
+  void* Xn = ar.take((size_t)n * chunk * eb);
+  float* part = (float*)ar.take(part_bytes);
   if (Xn == nullptr || part == nullptr)
     return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for H = Xt^T Xt");
   ProfScope prof(ctx, GANQ_K_HESSIAN);
-  for (int64_t k0 = 0; k0 < p; k0 += kTokenChunk) {
-    const int64_t pc = (p - k0 < kTokenChunk) ? p - k0 : kTokenChunk;
+  for (int64_t k0 = 0; k0 < p; k0 += chunk) {
+    const int64_t pc = (p - k0 < chunk) ? p - k0 : chunk;
     const int64_t pc8 = (pc + 7) / 8 * 8;                 // zero-padded tokens add nothing to H
     const char* src = (const char*)Xt + (size_t)k0 * ldxt * eb;
     GANQ_HIP(ctx, launch_transpose_tokens(s, src, eb, pc, n, ldxt, Xn, pc8));

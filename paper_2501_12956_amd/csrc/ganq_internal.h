@@ -66,6 +66,10 @@ size_t update_s_scratch_bytes(int64_t m, int64_t n);
 size_t update_t_scratch_bytes(int64_t m, int64_t n, int nbits);
 size_t loss_scratch_bytes(int64_t m, int64_t n);
 size_t cholesky_scratch_bytes(int64_t n);
+size_t outlier_scratch_bytes(int64_t m);
+hipError_t launch_outlier_split(hipStream_t s, const void* W, int w_is_f16, int64_t m, int64_t n, int64_t ldw,
+                                int lower, int upper, float* Wd, int64_t ldd, int64_t* row_ptr,
+                                int32_t* col_idx, float* values, int64_t capacity, void* scratch);
 
 // ---- kernel launchers (all enqueue on `s`, return the HIP error of the launch) ----
 

@@ -205,20 +205,23 @@ __global__ __launch_bounds__(256) void reduce_mirror_kernel(float* __restrict__ 
   }
 }
 
-// Xn[f][k] = Xt[k][f] for k < pc, 0 for pc <= k < ldn: tokens x features -> features x tokens
+// Xn[f][k] = Xt[k][f] for k < pc, 0 for pc <= k < ldn: tokens x features -> features x tokens.
+// 64 x 64 tiles through LDS; both sides move 128-byte row segments.
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_tokens_kernel(const T* __restrict__ Xt, int64_t pc,
                                                                int64_t n, int64_t ldxt,
                                                                T* __restrict__ Xn, int64_t ldn) {
-  __shared__ T tile[32][33];
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;          // 32 x 8
-  const int64_t k0 = (int64_t)blockIdx.x * 32, f0 = (int64_t)blockIdx.y * 32;
-  for (int r = ty; r < 32; r += 8) {
+  __shared__ T tile[64][66];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;          // 64 x 4
+  const int64_t k0 = (int64_t)blockIdx.x * 64, f0 = (int64_t)blockIdx.y * 64;
+#pragma unroll 4
+  for (int r = ty; r < 64; r += 4) {
     const int64_t k = k0 + r, f = f0 + tx;
     tile[r][tx] = (k < pc && f < n) ? Xt[k * ldxt + f] : (T)0;
   }
   __syncthreads();
-  for (int r = ty; r < 32; r += 8) {
+#pragma unroll 4
+  for (int r = ty; r < 64; r += 4) {
     const int64_t f = f0 + r, k = k0 + tx;
     if (f < n && k < ldn) Xn[f * ldn + k] = tile[tx][r];
   }
@@ -267,7 +270,7 @@ hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64
 
 hipError_t launch_transpose_tokens(hipStream_t s, const void* Xt, int elem_bytes, int64_t pc, int64_t n,
                                    int64_t ldxt, void* Xn, int64_t ldn) {
-  dim3 grid((unsigned)ceil_div(ldn, 32), (unsigned)ceil_div(n, 32));
+  dim3 grid((unsigned)ceil_div(ldn, 64), (unsigned)ceil_div(n, 64));
   if (elem_bytes == 2)
     hipLaunchKernelGGL(transpose_tokens_kernel<_Float16>, grid, dim3(256), 0, s, (const _Float16*)Xt, pc, n,
                        ldxt, (_Float16*)Xn, ldn);

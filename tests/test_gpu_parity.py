@@ -386,3 +386,91 @@ def test_quantize_layer_rank_deficient_activations(ctx, mode):
     l0 = ref.layer_loss(W64, H64, T0, Q0)[0]
     print("rank-deficient %s: loss %.4e vs nearest rounding onto T0 %.4e" % (mode, hist[-1], l0))
     assert hist[-1] < l0
+
+
+# ----------------------------------------------------------------------------- Algorithm 2
+@pytest.mark.parametrize("m,n,r,dtype", [(37, 300, 0.05, torch.float32), (8, 1000, 0.005, torch.float16),
+                                         (3, 64, 0.0, torch.float32), (5, 17, 0.3, torch.float16)])
+def test_outlier_split_matches_oracle(ctx, m, n, r, dtype):
+    """W = W_sparse + W_dense: no arithmetic on the values, so the split is compared exactly."""
+    g = torch.Generator().manual_seed(9)
+    W = (torch.randn(m, n, generator=g) * 0.02).to(dtype)
+    W[torch.rand(m, n, generator=g) < 0.01] *= 10.0
+    Ws_ref, Wd_ref = ref.outlier_split(W.numpy().astype(np.float64), r)
+    Wd, row_ptr, col, val = ctx.outlier_split(W.cuda(), r)
+    Wd = Wd.cpu().numpy().astype(np.float64)
+    assert np.array_equal(Wd, Wd_ref)
+    row_ptr, col, val = row_ptr.cpu().numpy(), col.cpu().numpy(), val.cpu().numpy().astype(np.float64)
+    assert row_ptr[0] == 0 and row_ptr[-1] == len(col) == len(val) == _count_masked(W.numpy().astype(np.float64), r)
+    dense = np.zeros((m, n))
+    for i in range(m):
+        cs = col[row_ptr[i]:row_ptr[i + 1]]
+        assert np.all(np.diff(cs) > 0)                  # ascending, no duplicates
+        dense[i, cs] = val[row_ptr[i]:row_ptr[i + 1]]
+    assert np.array_equal(dense, Ws_ref)
+    assert np.array_equal(dense + Wd, W.numpy().astype(np.float64))
+
+
+def _count_masked(W, r):
+    """Number of outlier positions of Algorithm 2 (zeros that fall in a tail count too)."""
+    n = W.shape[1]
+    p = 1.0 - 0.5 * r
+    upper = min(int(np.floor(n * p)), n - 1)
+    lower = int(np.ceil(n * (1.0 - p)))
+    Ws = np.sort(W, axis=1)
+    return int(((W >= Ws[:, upper][:, None]) | (W <= Ws[:, lower][:, None])).sum())
+
+
+def test_outlier_split_ties_and_capacity(ctx):
+    """Many equal values at a cut-off all become outliers (comparisons are >= and <=); a CSR
+    capacity that is too small is reported with the needed size, and nothing else changes."""
+    from paper_2501_12956_amd import binding as b
+    W = torch.zeros(4, 40)
+    W[:, :10] = -1.0
+    W[:, 30:] = 2.0
+    W[0, 5] = -3.0
+    Ws_ref, Wd_ref = ref.outlier_split(W.numpy().astype(np.float64), 0.1)
+    nnz_ref = _count_masked(W.numpy().astype(np.float64), 0.1)
+    assert nnz_ref == 4 * 20                             # all the -1 and all the 2 of every row
+    Wg = W.cuda()
+    with pytest.raises(b.GanqError) as exc:
+        Wd = torch.empty(4, 40, device="cuda")
+        rp = torch.empty(5, dtype=torch.int64, device="cuda")
+        col = torch.empty(8, dtype=torch.int32, device="cuda")
+        val = torch.empty(8, device="cuda")
+        import ctypes
+        nnz = ctypes.c_int64(0)
+        st = ctx.lib.ganq_outlier_split(ctx.handle, b._ptr(Wg), b.GANQ_F32, 4, 40, 40, 0.1, b._ptr(Wd), 40,
+                                        b._ptr(rp), b._ptr(col), b._ptr(val), 8, ctypes.byref(nnz))
+        assert st == b.GANQ_ERR_INVALID_ARG and nnz.value == nnz_ref
+        assert np.array_equal(Wd.cpu().numpy().astype(np.float64), Wd_ref)
+        ctx._check(st)
+    assert exc.value.status == b.GANQ_ERR_INVALID_ARG
+    Wd, row_ptr, col, val = ctx.outlier_split(Wg, 0.1, capacity=8)       # the binding retries
+    assert len(col) == nnz_ref and np.array_equal(Wd.cpu().numpy().astype(np.float64), Wd_ref)
+
+
+def test_outlier_split_lowers_the_layer_loss(ctx):
+    """Section 3.3: quantising W_dense and keeping W_sparse exact gives a lower layer error than
+    quantising W itself (config-1 recipe: 0.5 % of the weights are scaled by 10)."""
+    cfg = synth.CONFIGS["c1"]
+    W = synth.make_weight(cfg, 0, "cpu")
+    X = synth.make_activations(cfg, 0, "cpu")
+    H = ctx.build_hessian(X.cuda())
+    Wg = W.cuda()
+    T, Q, hist = ctx.quantize_layer(Wg, H, cfg.nbits, cfg.iters, history=True)
+    Wd, row_ptr, col, val = ctx.outlier_split(Wg, 0.005)
+    assert 0 < len(col) <= 0.02 * W.numel()
+    Td, Qd, histd = ctx.quantize_layer(Wd, H, cfg.nbits, cfg.iters, history=True)
+    # error of (T_d[Q_d] + W_sparse) against W equals the error of T_d[Q_d] against W_dense
+    H64 = H.cpu().numpy().astype(np.float64)
+    lsplit = ref.layer_loss(Wd.cpu().numpy().astype(np.float64), H64, Td.cpu().numpy(), Qd.cpu().numpy())[0]
+    Ws_ref, Wd_ref = ref.outlier_split(W.numpy().astype(np.float64), 0.005)
+    deq = ref.dequantize(Td.cpu().numpy().astype(np.float64), Qd.cpu().numpy()) + Ws_ref
+    R = W.numpy().astype(np.float64) - deq
+    ldirect = float(np.einsum("ij,jk,ik->", R, H64, R))
+    assert abs(lsplit - ldirect) <= 1e-9 * ldirect
+    assert abs(histd[-1] - lsplit) <= 1e-4 * lsplit
+    print("config 1: loss %.4e plain, %.4e with %.2f %% of the weights kept exact"
+          % (hist[-1], lsplit, 100.0 * len(col) / W.numel()))
+    assert lsplit < 0.8 * hist[-1]
