@@ -474,3 +474,24 @@ def test_outlier_split_lowers_the_layer_loss(ctx):
     print("config 1: loss %.4e plain, %.4e with %.2f %% of the weights kept exact"
           % (hist[-1], lsplit, 100.0 * len(col) / W.numel()))
     assert lsplit < 0.8 * hist[-1]
+
+
+def test_layers_sharing_activations_can_be_stacked(ctx):
+    """Layers that see the same input (q/k/v, gate/up) share H and L, and rows are independent
+    (Section 3.1): quantising their weights stacked row-wise in one call gives, row for row,
+    what separate calls give."""
+    n, nbits, K = 192, 4, 3
+    _, X = make_problem(8, n, 1024, nbits)
+    g = torch.Generator().manual_seed(17)
+    Ws = [(torch.randn(mm, n, generator=g) * 0.02).float().cuda() for mm in (40, 24, 9)]
+    H = ctx.build_hessian(X.cuda())
+    L, info = ctx.cholesky(H)
+    assert info == 0
+    Tall, Qall = ctx.quantize_layer(torch.cat(Ws, 0).contiguous(), H, nbits, K, L=L)
+    r0 = 0
+    for W in Ws:
+        T, Q = ctx.quantize_layer(W, H, nbits, K, L=L)
+        mm = W.shape[0]
+        assert torch.equal(Q, Qall[r0:r0 + mm])
+        assert torch.equal(T, Tall[r0:r0 + mm])
+        r0 += mm
