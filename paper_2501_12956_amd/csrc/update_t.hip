@@ -417,15 +417,29 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
   }
   __syncthreads();
   const double inv_s = (double)scale[1];
+  // M = sum of the per-group partial folds: coalesced reads, four running sums keep the loads
+  // of several groups in flight; then A = (M + M^T) / s + Diag(D)
+  __shared__ double Ms[16][17];
+  {
+    const int64_t gs = mpad * C * C;
+    for (int e = tid; e < C * C; e += 64) {
+      const float* __restrict__ P = Apart + i * C * C + e;
+      double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+      int g = 0;
+      for (; g + 4 <= ngroups; g += 4) {
+        s0 += (double)P[(int64_t)g * gs];
+        s1 += (double)P[(int64_t)(g + 1) * gs];
+        s2 += (double)P[(int64_t)(g + 2) * gs];
+        s3 += (double)P[(int64_t)(g + 3) * gs];
+      }
+      for (; g < ngroups; ++g) s0 += (double)P[(int64_t)g * gs];
+      Ms[e / C][e % C] = (s0 + s1) + (s2 + s3);
+    }
+  }
+  __syncthreads();
   for (int e = tid; e < C * C; e += 64) {
     const int a = e / C, b = e % C;
-    double lo = 0.0, up = 0.0;
-    for (int g = 0; g < ngroups; ++g) {
-      const float* __restrict__ P = Apart + ((int64_t)g * mpad + i) * C * C;
-      lo += (double)P[a * C + b];
-      up += (double)P[b * C + a];
-    }
-    double v = (lo + up) * inv_s;
+    double v = (Ms[a][b] + Ms[b][a]) * inv_s;
     if (a == b) { v += Dg[a]; diag0[a] = v; }
     A[a][b] = v;
   }
@@ -453,18 +467,21 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
     }
     __syncthreads();
   }
+  __shared__ double rdiagA[16];
+  if (tid < C) rdiagA[tid] = dead[tid] ? 0.0 : 1.0 / A[tid][tid];
+  __syncthreads();
   if (tid == 0) {
     double y[16];
     int nempty = 0;
     for (int a = 0; a < C; ++a) {
       double s = dead[a] ? 0.0 : rhs[a];
       for (int q = 0; q < a; ++q) s -= A[a][q] * y[q];
-      y[a] = dead[a] ? 0.0 : s / A[a][a];
+      y[a] = s * rdiagA[a];
     }
     for (int a = C - 1; a >= 0; --a) {
       double s = y[a];
       for (int q = a + 1; q < C; ++q) s -= A[q][a] * y[q];
-      y[a] = dead[a] ? 0.0 : s / A[a][a];
+      y[a] = s * rdiagA[a];
     }
     for (int a = 0; a < C; ++a) {
       if (dead[a]) {
