@@ -95,23 +95,26 @@ size_t quantize_scratch_bytes(int64_t m, int64_t n, int nbits) {
   b += update_t_scratch_bytes(m, n, nbits);
   b += loss_scratch_bytes(m, n);
   b += outlier_scratch_bytes(m);
+  b += gemm_split_scratch_bytes(m, n, n);
   return b + 8 * kAlign;
 }
 
 // row losses -> host double; scratch = [E][F][row values][double]
 ganq_status run_loss(ganq_ctx* ctx, Arena& ar, const float* W, int64_t m, int64_t n, int64_t ldw,
                      const float* H, int64_t ldh, const float* T, const uint8_t* Q, int64_t ldq,
-                     int nbits, double* loss_host, float* row_loss_out) {
+                     int nbits, double* loss_host, float* row_loss_out, void* gs = nullptr) {
+  if (gs == nullptr) gs = ar.take(gemm_split_scratch_bytes(m, n, n));
   float* E = (float*)ar.take((size_t)m * n * sizeof(float));
   float* F = (float*)ar.take((size_t)m * n * sizeof(float));
   float* rows = (float*)ar.take((size_t)m * sizeof(float));
   double* total = (double*)ar.take(sizeof(double));
-  if (E == nullptr || F == nullptr || rows == nullptr || total == nullptr)
+  if (gs == nullptr || E == nullptr || F == nullptr || rows == nullptr || total == nullptr)
     return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the loss evaluation");
   hipStream_t s = ctx->stream;
   ProfScope prof(ctx, GANQ_K_LOSS);
   GANQ_HIP(ctx, launch_residual(s, W, m, n, ldw, T, Q, ldq, nbits, E, n));
-  GANQ_HIP(ctx, launch_gemm_f32(s, 0, 0, m, n, n, 1.f, E, n, H, ldh, 0.f, F, n));
+  // F = E H; H is symmetric, so its rows serve as the rows of the right operand
+  GANQ_HIP(ctx, launch_gemm_split(s, m, n, n, E, n, H, ldh, F, n, gs, 0));
   float* rl = (row_loss_out != nullptr) ? row_loss_out : rows;
   GANQ_HIP(ctx, launch_rowdot(s, F, n, E, n, m, n, rl));
   GANQ_HIP(ctx, launch_sum_f64(s, rl, m, total));
@@ -455,12 +458,13 @@ ganq_status ganq_update_T(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, i
   Arena ar(ctx->ws, ctx->ws_bytes);
   float* G = (float*)ar.take((size_t)m * n * sizeof(float));
   void* scratch = ar.take(update_t_scratch_bytes(m, n, nbits));
-  if (G == nullptr || scratch == nullptr)
+  void* gs = ar.take(gemm_split_scratch_bytes(m, n, n));
+  if (G == nullptr || scratch == nullptr || gs == nullptr)
     return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the T-update");
   hipStream_t s = ctx->stream;
   {
     ProfScope prof(ctx, GANQ_K_GEMM_WH);
-    GANQ_HIP(ctx, launch_gemm_f32(s, 0, 0, m, n, n, 1.f, W, ldw, H, ldh, 0.f, G, n));
+    GANQ_HIP(ctx, launch_gemm_split(s, m, n, n, W, ldw, H, ldh, G, n, gs, 0));
   }
   {
     ProfScope prof(ctx, GANQ_K_T_PREP);
@@ -569,12 +573,13 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   float* G = (float*)ar.take((size_t)m * n * sizeof(float));
   void* s_scratch = ar.take(update_s_scratch_bytes(m, n));
   void* t_scratch = ar.take(update_t_scratch_bytes(m, n, nbits));
-  if (G == nullptr || s_scratch == nullptr || t_scratch == nullptr)
+  void* gs = ar.take(gemm_split_scratch_bytes(m, n, n));
+  if (G == nullptr || s_scratch == nullptr || t_scratch == nullptr || gs == nullptr)
     return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small (solver scratch)");
   if (iters > 0) {
     {
       ProfScope prof(ctx, GANQ_K_GEMM_WH);
-      GANQ_HIP(ctx, launch_gemm_f32(s, 0, 0, m, n, n, 1.f, Wf, ldwf, H, ldh, 0.f, G, n));
+      GANQ_HIP(ctx, launch_gemm_split(s, m, n, n, Wf, ldwf, H, ldh, G, n, gs, 0));
     }
     // the fp16 split of H is made once per layer
     ProfScope prof(ctx, GANQ_K_T_PREP);
@@ -588,7 +593,7 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
     }
     if (loss_history_host != nullptr) {
       Arena sub((char*)ctx->ws + align_up(ar.off), ctx->ws_bytes - align_up(ar.off));
-      st = run_loss(ctx, sub, Wf, m, n, ldwf, H, ldh, T, Q, ldq, nbits, &loss_history_host[2 * k], nullptr);
+      st = run_loss(ctx, sub, Wf, m, n, ldwf, H, ldh, T, Q, ldq, nbits, &loss_history_host[2 * k], nullptr, gs);
       if (st != GANQ_OK) return st;
     }
     {
@@ -605,7 +610,7 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
     }
     if (loss_history_host != nullptr) {
       Arena sub((char*)ctx->ws + align_up(ar.off), ctx->ws_bytes - align_up(ar.off));
-      st = run_loss(ctx, sub, Wf, m, n, ldwf, H, ldh, T, Q, ldq, nbits, &loss_history_host[2 * k + 1], nullptr);
+      st = run_loss(ctx, sub, Wf, m, n, ldwf, H, ldh, T, Q, ldq, nbits, &loss_history_host[2 * k + 1], nullptr, gs);
       if (st != GANQ_OK) return st;
     }
   }

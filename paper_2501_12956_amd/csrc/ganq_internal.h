@@ -67,6 +67,9 @@ size_t update_t_scratch_bytes(int64_t m, int64_t n, int nbits);
 size_t loss_scratch_bytes(int64_t m, int64_t n);
 size_t cholesky_scratch_bytes(int64_t n);
 size_t outlier_scratch_bytes(int64_t m);
+size_t gemm_split_scratch_bytes(int64_t M, int64_t N, int64_t K);
+hipError_t launch_gemm_split(hipStream_t s, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda,
+                             const float* B, int64_t ldb, float* C, int64_t ldc, void* scratch, int b_ready);
 hipError_t launch_outlier_split(hipStream_t s, const void* W, int w_is_f16, int64_t m, int64_t n, int64_t ldw,
                                 int lower, int upper, float* Wd, int64_t ldd, int64_t* row_ptr,
                                 int32_t* col_idx, float* values, int64_t capacity, void* scratch);
