@@ -37,15 +37,15 @@ PEAK_F32_ADD_TOPS = 78.6
 # reading of a plain 1 GiB copy: x2.000 and x1.000); copied from profiles/bench_c3_hbm_traffic.txt,
 # which gives the commands.  Other configs report null.
 TRAFFIC_C3_BYTES = {
-    "hessian": (18130.93 + 513.00 + 516.05 + 64.09) * 2 ** 20,     # product kernel + reduction
-    "update_s": 1994.91 * 2 ** 20,
-    "t_accum": 819.93 * 2 ** 20,
-    "t_solve": 265.70 * 2 ** 20,
+    "hessian": (18506.65 + 580.14) * 2 ** 20,     # product kernel + reduction
+    "update_s": 1995.06 * 2 ** 20,
+    "t_accum": 820.03 * 2 ** 20,
+    "t_solve": 144.63 * 2 ** 20,
     "t_pad": 64.02 * 2 ** 20,
-    "gemm_wh": 806.44 * 2 ** 20,
-    "loss": (806.44 + 146.03 + 128.15) * 2 ** 20,
-    "init": (96.02 + 64.30) * 2 ** 20,
-    "cholesky": (96.27 + 126 * 13.26 + 64 * 0.06) * 2 ** 20,
+    "gemm_wh": (946.24 + 2 * 64.05 + 2 * 128.01) * 2 ** 20,     # piece product + 2 x (absmax, split)
+    "loss": (946.24 + 2 * 64.05 + 2 * 128.01 + 146.03 + 128.15) * 2 ** 20,
+    "init": (96.02 + 64.28) * 2 ** 20,
+    "cholesky": (128.34 + 15 * 34.83 + 64 * 2.27) * 2 ** 20,
     "t_prep": (65.24 + 0.52) * 2 ** 20,
 }
 
@@ -57,13 +57,14 @@ def kernel_work(cls, m, n, p, nbits, iters):
     if cls == "cholesky":
         return "mfma", float(n) ** 3 / 3.0, "TFLOP/s", PEAK_F32_MFMA_TFLOPS
     if cls == "gemm_wh":
-        return "mfma", 2.0 * m * n * n, "TFLOP/s", PEAK_F32_MFMA_TFLOPS
+        # runs as three fp16 piece products; one product's flops are counted
+        return "mfma", 2.0 * m * n * n, "TFLOP/s", PEAK_F16_TFLOPS
     if cls == "update_s":
         return "mfma", float(m) * n * n, "TFLOP/s", PEAK_F32_MFMA_TFLOPS      # triangular: m n^2 / 2 MACs
     if cls == "t_accum":
         return "alu", 0.5 * m * n * n, "TFLOP/s", PEAK_F32_ADD_TOPS           # m n^2 / 2 additions
     if cls == "loss":
-        return "mfma", 2.0 * m * n * n, "TFLOP/s", PEAK_F32_MFMA_TFLOPS
+        return "mfma", 2.0 * m * n * n, "TFLOP/s", PEAK_F16_TFLOPS
     if cls == "t_prep":
         return "hbm", 4.0 * n * n / 2 + 4.0 * n * n / 2, "GB/s", PEAK_HBM_GBS  # read tril(H), write 2 fp16 halves
     if cls == "t_pad":

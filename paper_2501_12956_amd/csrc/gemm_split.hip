@@ -49,10 +49,12 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ X
                                                      int64_t ld, unsigned* __restrict__ amax) {
   __shared__ float red[256];
   float mx = 0.f;
-  const int64_t total = rows * cols;
-  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-    const float v = fabsf(X[(e / cols) * ld + e % cols]);
-    if (v < __builtin_huge_valf() && v > mx) mx = v;
+  for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+    const float* __restrict__ xr = X + r * ld;
+    for (int64_t k = threadIdx.x; k < cols; k += 256) {
+      const float v = fabsf(xr[k]);
+      if (v < __builtin_huge_valf() && v > mx) mx = v;
+    }
   }
   red[threadIdx.x] = mx;
   __syncthreads();
@@ -220,13 +222,13 @@ hipError_t launch_gemm_split(hipStream_t s, int64_t M, int64_t N, int64_t K, con
   // amax words are cleared by a small kernel (capturable, unlike a memset node)
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, amax, b_ready ? 1 : 2, 0u);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(absmax_kernel, dim3(512), dim3(256), 0, s, A, M, K, lda, amax);
+  hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)(M < 2048 ? M : 2048)), dim3(256), 0, s, A, M, K, lda, amax);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(split_kernel, dim3((unsigned)ceil_div(k64, 256), (unsigned)M), dim3(256), 0, s, A, M, K, lda,
                      amax, As, k64);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (!b_ready) {
-    hipLaunchKernelGGL(absmax_kernel, dim3(512), dim3(256), 0, s, B, N, K, ldb, amax + 1);
+    hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)(N < 2048 ? N : 2048)), dim3(256), 0, s, B, N, K, ldb, amax + 1);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(split_kernel, dim3((unsigned)ceil_div(k64, 256), (unsigned)N), dim3(256), 0, s, B, N, K,
                        ldb, amax + 1, Bs, k64);
