@@ -115,7 +115,7 @@ hipError_t launch_t_solve(hipStream_t s, const float* G, int64_t ldg, int64_t m,
                           int32_t* empty_count, void* scratch);
 
 // row_loss[i] = sum_j F_ij * E_ij with E = W - T[Q] written to Ebuf first (launch_residual),
-// F = E * H by launch_gemm_f32, then launch_rowdot.
+// F = E * H by launch_gemm_split, then launch_rowdot.
 hipError_t launch_residual(hipStream_t s, const float* W, int64_t m, int64_t n, int64_t ldw,
                            const float* T, const uint8_t* Q, int64_t ldq, int nbits, float* E,
                            int64_t lde);

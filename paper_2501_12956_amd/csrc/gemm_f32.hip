@@ -1,9 +1,8 @@
 // fp32 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x2_f32).
 //
-// Serves the GEMM-shaped fp32 steps of the GANQ layer solver: G = W H for the
-// right-hand sides of the T-update (Eq. (7)), F = E H for the objective in the
-// form of Eq. (9), the trailing updates of the blocked Cholesky factorisation
-// (Eq. (10)) and H = X X^T for fp32 activations.
+// Serves the steps of the GANQ layer solver that need exact fp32 products: the
+// trailing updates of the blocked Cholesky factorisation (Eq. (10)) and
+// H = X X^T for fp32 activations (Eq. (9)).
 //
 // Workgroup tile 128 x 128 x 16, 256 threads = 4 wavefronts in a 2 x 2 grid,
 // each wavefront owning a 64 x 64 sub-tile as 2 x 2 MFMA tiles of 32 x 32.

@@ -1,6 +1,6 @@
 // Objective of Eq. (1) in the form of Eq. (9): sum_i E_i H E_i^T, E = W - T[Q].
-// E is formed here, F = E H comes from the fp32 matrix-core GEMM, and the row
-// values sum_j F_ij E_ij are reduced per row in float64 and then over rows.
+// E is formed here, F = E H comes from the split-fp16 matrix-core GEMM, and the
+// row values sum_j F_ij E_ij are reduced per row in float64 and then over rows.
 #include "ganq_internal.h"
 
 namespace ganq {

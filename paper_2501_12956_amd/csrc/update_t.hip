@@ -8,8 +8,8 @@
 //   Z[j, (i,b)] = sum_{k<j} H_jk [Q_ik == b]
 //
 // is a GEMM whose left operand is the strictly lower triangle of H and whose
-// right operand is the one-hot expansion of Q, generated on the fly from the
-// index bytes.  One-hot entries are exact in fp16; H is split into two fp16
+// right operand is the one-hot expansion of Q, kept in LDS and updated in place
+// from precomputed positions.  One-hot entries are exact in fp16; H is split into two fp16
 // pieces (hi + lo, 22 significant bits, pre-scaled by a power of two so that the
 // largest entry sits near 2^15), both accumulated in fp32 by
 // v_mfma_f32_32x32x16_f16.  Only k < j is visited (H is symmetric):
