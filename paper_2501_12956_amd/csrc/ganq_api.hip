@@ -77,6 +77,8 @@ void prof_drain(ganq_ctx* ctx) {
 }
 
 bool nbits_ok(int nbits) { return nbits >= 1 && nbits <= 4; }
+// several kernels put a matrix dimension on the y axis of the launch grid
+constexpr int64_t kMaxDim = 65535;
 bool dtype_ok(int d) { return d == GANQ_F16 || d == GANQ_F32; }
 
 ganq_status bind_device(ganq_ctx* ctx) {
@@ -387,6 +389,7 @@ ganq_status ganq_cholesky(ganq_ctx* ctx, const float* H, int64_t n, int64_t ldh,
   GANQ_REQUIRE(ctx, precond >= GANQ_PRECOND_NONE && precond <= GANQ_PRECOND_AUTO, "precond");
   GANQ_REQUIRE(ctx, precond != GANQ_PRECOND_LAMBDA || (lambda > 0.f && std::isfinite(lambda)),
                "lambda must be positive and finite");
+  if (n > kMaxDim) return fail(ctx, GANQ_ERR_UNSUPPORTED, "n must not exceed 65535");
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
   Arena ar(ctx->ws, ctx->ws_bytes);
@@ -453,6 +456,7 @@ ganq_status ganq_update_T(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, i
   GANQ_REQUIRE(ctx, ldw >= n && ldq >= n, "ldw / ldq");
   GANQ_REQUIRE(ctx, empty == GANQ_EMPTY_ZERO || empty == GANQ_EMPTY_KEEP, "empty");
   if (m == 0) return GANQ_OK;
+  if (m > kMaxDim || n > kMaxDim) return fail(ctx, GANQ_ERR_UNSUPPORTED, "m and n must not exceed 65535");
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
   Arena ar(ctx->ws, ctx->ws_bytes);
@@ -498,6 +502,7 @@ ganq_status ganq_layer_loss(ganq_ctx* ctx, const float* W, int64_t m, int64_t n,
   GANQ_REQUIRE(ctx, ldw >= n && ldq >= n, "ldw / ldq");
   *loss_host = 0.0;
   if (m == 0) return GANQ_OK;
+  if (m > kMaxDim || n > kMaxDim) return fail(ctx, GANQ_ERR_UNSUPPORTED, "m and n must not exceed 65535");
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
   Arena ar(ctx->ws, ctx->ws_bytes);
@@ -539,6 +544,7 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   if ((uint64_t)n * (uint64_t)(L != nullptr ? ldl : n) * sizeof(float) >= (1ull << 32))
     return fail(ctx, GANQ_ERR_UNSUPPORTED, "the S-update addresses L with 32-bit byte offsets: n * ldl * 4 must stay below 4 GiB");
   if (m == 0) return GANQ_OK;
+  if (m > kMaxDim || n > kMaxDim) return fail(ctx, GANQ_ERR_UNSUPPORTED, "m and n must not exceed 65535");
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
   hipStream_t s = ctx->stream;
