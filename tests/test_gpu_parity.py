@@ -495,3 +495,41 @@ def test_layers_sharing_activations_can_be_stacked(ctx):
         assert torch.equal(Q, Qall[r0:r0 + mm])
         assert torch.equal(T, Tall[r0:r0 + mm])
         r0 += mm
+
+
+# ----------------------------------------------------------------------------- seeded shape sweep
+def _sweep_shapes():
+    """Shapes that straddle the kernels' tile edges (16-row slabs, 64-column blocks, 128 x 512
+    accumulation tiles, 256-column panels) without being multiples of any of them."""
+    shapes = [(1, 2, 1), (15, 63, 4), (17, 66, 3), (31, 127, 2), (100, 255, 4), (129, 258, 3),
+              (260, 513, 4), (17, 640, 2), (31, 777, 3), (129, 777, 4), (260, 66, 1)]
+    return [(m, n, nbits, 37 * i + 1) for i, (m, n, nbits) in enumerate(shapes)]
+
+
+@pytest.mark.parametrize("m,n,nbits,seed", _sweep_shapes())
+def test_pipeline_shape_sweep(ctx, m, n, nbits, seed):
+    """Two iterations of the whole path on an odd shape; each stage against the float64 definition."""
+    W, X = make_problem(m, n, 3 * n + 40, nbits, seed=seed)
+    Wg = W.cuda()
+    H = ctx.build_hessian(X.cuda())
+    check_H(H.cpu().numpy().astype(np.float64), ref.build_hessian(X.numpy()), X.shape[1], "sweep")
+    L, info = ctx.cholesky(H)
+    assert info == 0
+    H64 = H.cpu().numpy().astype(np.float64)
+    L64 = L.cpu().numpy().astype(np.float64)
+    W64 = W.numpy().astype(np.float64)
+    Lref = np.linalg.cholesky(H64)
+    assert np.linalg.norm(L64 - Lref) <= 1e-4 * np.linalg.norm(Lref)
+    assert not np.any(np.triu(L64, 1))
+    T1, _ = ctx.quantize_layer(Wg, H, nbits, 1, L=L)
+    T2, Q2, hist = ctx.quantize_layer(Wg, H, nbits, 2, L=L, history=True)
+    _, _, viol = check_S(W64, L64, T1.cpu().numpy().astype(np.float64), Q2.cpu().numpy(),
+                         "sweep %dx%d N=%d" % (m, n, nbits))
+    assert viol == 0
+    Tref, _ = ref.update_T(W64, H64, Q2.cpu().numpy(), nbits, T_prev=T1.cpu().numpy().astype(np.float64))
+    scale = np.maximum(np.abs(Tref).max(axis=1), 1e-300)
+    assert np.all(np.abs(T2.cpu().numpy() - Tref).max(axis=1) / scale <= 1e-4)
+    lref = ref.layer_loss(W64, H64, T2.cpu().numpy(), Q2.cpu().numpy())[0]
+    base = float(((W64 @ H64) * W64).sum())          # ||W X||^2: the scale of fp32 noise when the fit is exact
+    assert abs(hist[-1] - lref) <= 1e-4 * lref + 1e-6 * base
+    assert hist[3] <= hist[2] * (1 + 1e-5) + 1e-6 * base
