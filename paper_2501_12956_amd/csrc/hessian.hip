@@ -51,28 +51,69 @@ __device__ inline int4v make_rsrc(const void* base, int64_t bytes) {
   return r;
 }
 
+// Tiles (r, c), c <= r < nt, of the lower triangle in Z-order (bits of c and r interleaved, c
+// lowest): the t-th one, found by descending the quadtree with closed-form counts.
+__device__ inline int zorder_box_count(int r0, int c0, int s, int nt) {
+  // pairs with r0 <= r < min(r0 + s, nt), c0 <= c < c0 + s, c <= r: row r holds
+  // clamp(r - c0 + 1, 0, s) of them
+  const int r1 = (r0 + s < nt) ? r0 + s : nt;
+  if (r1 <= r0) return 0;
+  const int a = (r0 > c0) ? r0 : c0;
+  const int b = (r1 < c0 + s - 1) ? r1 : c0 + s - 1;
+  int cnt = 0;
+  if (b > a) cnt += (b - a) * (a + b - 2 * c0 + 1) / 2;
+  const int f = (r0 > c0 + s - 1) ? r0 : c0 + s - 1;
+  if (r1 > f) cnt += (r1 - f) * s;
+  return cnt;
+}
+
+__device__ inline void zorder_tile(int t, int nt, int& bm, int& bn) {
+  int s = 1;
+  while (s < nt) s <<= 1;
+  int r0 = 0, c0 = 0;
+  while (s > 1) {
+    s >>= 1;
+    int cnt = zorder_box_count(r0, c0, s, nt);
+    if (t >= cnt) {
+      t -= cnt;
+      cnt = zorder_box_count(r0, c0 + s, s, nt);
+      if (t < cnt) {
+        c0 += s;
+      } else {
+        t -= cnt;
+        cnt = zorder_box_count(r0 + s, c0, s, nt);
+        r0 += s;
+        if (t >= cnt) {
+          t -= cnt;
+          c0 += s;
+        }
+      }
+    }
+  }
+  bm = r0;
+  bn = c0;
+}
+
 // 8 wavefronts (2 per SIMD) in a 2 x 4 grid, each owning 128 x 64 of the tile as 4 x 2 MFMA
 // tiles of 32 x 32 (128 accumulator registers).  Two LDS stages of 64 tokens, one barrier
 // per stage: after the barrier the loads of the next stage are issued into the buffer that
 // every wavefront has just finished reading, then the current stage is multiplied.
 __global__ __launch_bounds__(64 * HNW) void hessian_f16_kernel(const _Float16* __restrict__ X, int64_t n,
                                                               int64_t p, int64_t ldx, int64_t chunk,
-                                                              int ntiles, int nsplit,
-                                                              float* __restrict__ partials) {
-  // Workgroups are dealt to the 8 XCDs round-robin by their flat index.  All XCDs work on
-  // the same token split at the same time, so that the slice of X in flight fits the
-  // memory-side cache, and XCD x takes a contiguous run of the split's tiles, which share
-  // row blocks of X through its L2.
-  const int tpx = (ntiles + 7) / 8;
-  const int q = blockIdx.x >> 3, xcd = blockIdx.x & 7;
-  const int split = q / tpx;
-  // triangular tile index -> (bm, bn), bn <= bm
-  const int t = xcd * tpx + q % tpx;
-  if (split >= nsplit || t >= ntiles) return;
-  int bm = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
-  while ((int64_t)(bm + 1) * (bm + 2) / 2 <= t) ++bm;
-  while ((int64_t)bm * (bm + 1) / 2 > t) --bm;
-  const int bn = t - (int)((int64_t)bm * (bm + 1) / 2);
+                                                              int nt, int ntiles, int ngroups, int gsz,
+                                                              int nsplit, float* __restrict__ partials) {
+  // Workgroups are dealt to the 8 XCDs round-robin by their flat index, so the 32 workgroups
+  // with consecutive (blockIdx.x >> 3) run side by side on one XCD.  They take one group of at
+  // most 32 tiles of one token split, and the groups are runs of the Z-order of the triangle:
+  // a group touches few distinct row blocks of X (8 to 12 for 32 tiles), which its workgroups
+  // then share through the XCD's L2 instead of each fetching its own pair.
+  const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+  const int item = (q >> 5) * 8 + xcd, w = q & 31;
+  const int split = item / ngroups;
+  const int t = (item - split * ngroups) * gsz + w;
+  if (split >= nsplit || w >= gsz || t >= ntiles) return;
+  int bm, bn;
+  zorder_tile(t, nt, bm, bn);
   const int64_t kbeg = (int64_t)split * chunk;
   const int64_t kend = (kbeg + chunk < p) ? kbeg + chunk : p;
 
@@ -250,7 +291,8 @@ hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64
   int64_t chunk = ceil_div(ceil_div(p, split), HK) * HK;
   const int64_t nt = ceil_div(n, HT);
   const int ntiles = (int)(nt * (nt + 1) / 2);
-  dim3 grid((unsigned)(8 * ceil_div(ntiles, 8) * split));
+  const int ngroups = (int)ceil_div(ntiles, 32), gsz = (int)ceil_div(ntiles, ngroups);
+  dim3 grid((unsigned)(8 * ceil_div((int64_t)ngroups * split, 8) * 32));
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t ea = hipFuncSetAttribute((const void*)hessian_f16_kernel,
@@ -259,7 +301,7 @@ hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64
     attr_set = true;
   }
   hipLaunchKernelGGL(hessian_f16_kernel, grid, dim3(64 * HNW), HS * HSTAGEB, s, X, n, p, ldx, chunk,
-                     ntiles, split, partials);
+                     (int)nt, ntiles, ngroups, gsz, split, partials);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   dim3 g2((unsigned)ceil_div(n, 32), (unsigned)ceil_div(n, 32));
