@@ -23,6 +23,9 @@ Pinned (see the CPU test-suite):
   quantize_layer  half-step monotonicity of the T-step, restartability,
                   scaling invariances
   lut_storage_fraction   Table 1 printed percentages
+  pack_codes      hand-written byte patterns, round trip, Table 1 byte counts
+  lut_matvec      unit vectors pick single table entries, constant tables give
+                  scaled sums, explicit triple loop on tiny cases
 End-to-end solver outputs: parity unpinned by the paper (it prints no
 solver-level numbers); only the self-consistency pins above apply.
 """
@@ -345,3 +348,47 @@ def uniform_storage_fraction(m, n, nbits=4):
     """Per-channel uniform quantisation (fp16 scale + zero point per row),
     Table 1: (0.5mn + 4m) / (2mn) at 4 bits."""
     return (nbits / 8.0 * m * n + 4.0 * m) / (2.0 * m * n)
+
+
+# --------------------------------------------------------------------------
+# Deployment format and LUT-based product      Table 1, Figure 1(a), Section 4.4
+# --------------------------------------------------------------------------
+def packed_row_bytes(n, nbits):
+    """Bytes of one row of N-bit codes: ceil(n N / 8) (0.5 n at 4 bits, Table 1)."""
+    return (n * nbits + 7) // 8
+
+
+def pack_codes(Q, nbits):
+    """Row i of Q as a little-endian bit stream: code j occupies bits
+    [N j, N j + N) of the row, bit b of the stream being bit (b mod 8) of byte
+    b // 8; the last byte is padded with zero bits.  Returns uint8 (m, ceil(nN/8))."""
+    Q = np.asarray(Q)
+    m, n = Q.shape
+    assert Q.max(initial=0) < (1 << nbits)
+    bits = ((Q.astype(np.int64)[:, :, None] >> np.arange(nbits)) & 1).astype(np.uint8)
+    return np.packbits(bits.reshape(m, n * nbits), axis=1, bitorder="little")
+
+
+def unpack_codes(P, n, nbits):
+    """Inverse of pack_codes."""
+    P = np.asarray(P, dtype=np.uint8)
+    bits = np.unpackbits(P, axis=1, bitorder="little")[:, : n * nbits]
+    bits = bits.reshape(P.shape[0], n, nbits).astype(np.int64)
+    return (bits << np.arange(nbits)).sum(axis=2).astype(np.uint8)
+
+
+def lut_table_fp16(T):
+    """The stored per-row table: T rounded to fp16 (2 bytes per entry, Table 1)."""
+    return np.asarray(T, dtype=np.float64).astype(np.float16)
+
+
+def lut_matvec(T16, Q, x, W_sparse=None):
+    """y_i = sum_j T16_i[Q_ij] x_j (+ (W_sparse x)_i): the look-up-table product
+    of Figure 1(a) for one activation vector (batch 1, Section 4.4), with the
+    outlier part of GANQ* added as a separate sparse product.  T16 holds the
+    fp16 table values, x the fp16 activations; the sums are float64."""
+    Wq = dequantize(_f64(T16), Q)
+    y = Wq @ _f64(x)
+    if W_sparse is not None:
+        y = y + _f64(W_sparse) @ _f64(x)
+    return y

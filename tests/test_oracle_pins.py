@@ -371,3 +371,63 @@ def test_storage_model_matches_table1():
         m, n = int(m), int(n)
         assert round(100 * ref.uniform_storage_fraction(m, n), 2) == float(uni)
         assert round(100 * ref.lut_storage_fraction(m, n), 2) == float(lut)
+
+
+# ------------------------------------------------------------------ deployment format
+def test_pack_codes_hand_written_bytes():
+    # 4 bits: two codes per byte, the even column in the low nibble
+    P = ref.pack_codes(np.array([[0x1, 0x2, 0xF, 0x0, 0x7]], dtype=np.uint8), 4)
+    assert P.tolist() == [[0x21, 0x0F, 0x07]]
+    # 3 bits: 8 codes fill 3 bytes; codes 1..7,0 -> bit stream 001 010 011 100 101 110 111 000 (LSB first)
+    # byte0 = c0 | c1<<3 | (c2&3)<<6 = 1 | 16 | 192 = 0xD1; byte1 = c2>>2 | c3<<1 | c4<<4 | (c5&1)<<7 = 0|8|80|0 = 0x58
+    # byte2 = c5>>1 | c6<<2 | c7<<5 = 3 | 28 | 0 = 0x1F
+    P = ref.pack_codes(np.array([[1, 2, 3, 4, 5, 6, 7, 0]], dtype=np.uint8), 3)
+    assert P.tolist() == [[0xD1, 0x58, 0x1F]]
+    # 2 bits and 1 bit
+    assert ref.pack_codes(np.array([[3, 0, 1, 2, 2]], dtype=np.uint8), 2).tolist() == [[0x93, 0x02]]
+    assert ref.pack_codes(np.array([[1, 0, 0, 1, 1, 1, 0, 0, 1]], dtype=np.uint8), 1).tolist() == [[0x39, 0x01]]
+
+
+@pytest.mark.parametrize("nbits", [1, 2, 3, 4])
+def test_pack_codes_round_trip_and_table1_bytes(nbits):
+    rng = np.random.default_rng(nbits)
+    for n in (1, 7, 8, 31, 32, 33, 100):
+        Q = rng.integers(0, 1 << nbits, size=(5, n)).astype(np.uint8)
+        P = ref.pack_codes(Q, nbits)
+        assert P.shape == (5, ref.packed_row_bytes(n, nbits))
+        assert np.array_equal(ref.unpack_codes(P, n, nbits), Q)
+    # Table 1: codes plus a 2-byte table entry per code value make 0.5 m n + 32 m bytes at 4 bits
+    for m, n in ((2048, 2048), (4096, 4096), (8192, 8192)):
+        total = m * ref.packed_row_bytes(n, 4) + m * 16 * 2
+        assert total == 0.5 * m * n + 32 * m
+        assert total / (2.0 * m * n) == ref.lut_storage_fraction(m, n)
+
+
+def test_lut_matvec_special_cases_and_brute_force():
+    rng = np.random.default_rng(3)
+    m, n, nbits = 6, 19, 3
+    C = 1 << nbits
+    T16 = ref.lut_table_fp16(rng.normal(size=(m, C)))
+    assert T16.dtype == np.float16
+    Q = rng.integers(0, C, size=(m, n)).astype(np.uint8)
+    # a unit vector picks one table entry per row
+    for j in (0, 7, n - 1):
+        e = np.zeros(n, dtype=np.float16)
+        e[j] = 1
+        assert np.array_equal(ref.lut_matvec(T16, Q, e), T16[np.arange(m), Q[:, j]].astype(np.float64))
+    # a table constant along each row gives that constant times sum(x)
+    x = rng.normal(size=n).astype(np.float16)
+    Tc = np.repeat(T16[:, :1], C, axis=1)
+    assert np.allclose(ref.lut_matvec(Tc, Q, x), Tc[:, 0].astype(np.float64) * x.astype(np.float64).sum(),
+                       rtol=0, atol=1e-12)
+    # explicit loops, with a sparse part
+    Ws = np.zeros((m, n))
+    Ws[1, 4], Ws[5, 0], Ws[5, 18] = 2.5, -1.25, 0.75
+    y = ref.lut_matvec(T16, Q, x, Ws)
+    for i in range(m):
+        acc = 0.0
+        for j in range(n):
+            acc += float(T16[i, Q[i, j]]) * float(x[j]) + Ws[i, j] * float(x[j])
+        assert abs(y[i] - acc) <= 1e-12 * max(1.0, abs(acc))
+    # the product of the table look-up equals the product with the dequantised matrix of Eq. (1)
+    assert np.array_equal(ref.lut_matvec(T16, Q, x), ref.dequantize(T16, Q) @ x.astype(np.float64))
