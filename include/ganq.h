@@ -194,6 +194,35 @@ ganq_status ganq_outlier_split(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype,
                                int64_t ldw, double r, float* W_dense, int64_t ldd, int64_t* row_ptr,
                                int32_t* col_idx, float* values, int64_t capacity, int64_t* nnz_host);
 
+/* ---- deployment: stored form and look-up-table product ---------------------- */
+
+/* Stored form of a quantized layer (Table 1): per row the n N-bit codes and a
+ * table of 2^N fp16 values (0.5 m n + 32 m bytes at 4 bits when n is a multiple
+ * of 32).  Codes: row i starts at packed + i * ldp bytes and is a little-endian
+ * bit stream, code j in bits [N j, N j + N), bit b of the stream being bit
+ * (b mod 8) of byte b / 8; unused bits up to ganq_packed_row_bytes() are zero.
+ * ganq_packed_row_bytes = 4 N ceil(n / 32), rounded up to a multiple of 16. */
+int64_t ganq_packed_row_bytes(int64_t n, int nbits);
+
+/* Q (m x n codes, device) and T (m x 2^N fp32, device) -> packed (m rows of ldp
+ * bytes, device, 16-byte aligned, ldp % 16 == 0, ldp >= ganq_packed_row_bytes)
+ * and lut (m x 2^N IEEE binary16 bit patterns, device; T rounded to nearest
+ * even).  1 <= nbits <= 4, m <= 65535.  Asynchronous on the context's stream. */
+ganq_status ganq_pack_layer(ganq_ctx* ctx, const uint8_t* Q, int64_t m, int64_t n, int64_t ldq,
+                            const float* T, int nbits, uint8_t* packed, int64_t ldp, uint16_t* lut);
+
+/* y = W~ x (+ W_sparse x), W~_ij = lut_i[Q_ij]: the look-up-table product of
+ * Figure 1(a) for one activation vector (batch-1 decoding, Section 4.4), with
+ * the sparse part of GANQ* (Section 3.3) when row_ptr != NULL.  packed / ldp /
+ * lut as written by ganq_pack_layer; x: n fp16 values (device); y: m fp32
+ * (device); row_ptr (m + 1, int64), col_idx (int32, each < n) and values (fp32)
+ * are the CSR arrays of ganq_outlier_split (device) or all NULL.  fp16 x fp16
+ * products, fp32 accumulation; the result is bit-reproducible.  Asynchronous on
+ * the context's stream; uses no workspace. */
+ganq_status ganq_lut_gemv(ganq_ctx* ctx, const uint8_t* packed, int64_t ldp, const uint16_t* lut,
+                          int nbits, int64_t m, int64_t n, const void* x, float* y,
+                          const int64_t* row_ptr, const int32_t* col_idx, const float* values);
+
 /* ---- optional per-kernel timing (measurement aid, not part of the method) ------ */
 
 /* Kernel classes the library launches; one step of Algorithm 1 touches all of them. */
@@ -209,7 +238,9 @@ typedef enum {
   GANQ_K_T_SOLVE = 8,  /* per-row assembly and solve, once per sweep */
   GANQ_K_LOSS = 9,     /* objective evaluation */
   GANQ_K_OUTLIER = 10, /* outlier split (sort, offsets, compaction) */
-  GANQ_K_COUNT = 11
+  GANQ_K_PACK = 11,    /* stored form: bit packing and fp16 tables */
+  GANQ_K_LUT_GEMV = 12,/* look-up-table product for one activation vector */
+  GANQ_K_COUNT = 13
 } ganq_kernel_class;
 
 /* on != 0: bracket every kernel class launched through this context with HIP

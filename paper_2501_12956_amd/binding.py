@@ -25,10 +25,11 @@ EXPORTS = ["ganq_create", "ganq_destroy", "ganq_workspace_bytes", "ganq_set_work
            "ganq_status_string", "ganq_last_error", "ganq_build_hessian", "ganq_build_hessian_tokens",
            "ganq_cholesky",
            "ganq_init_codebooks", "ganq_update_S", "ganq_update_T", "ganq_layer_loss",
-           "ganq_quantize_layer", "ganq_outlier_split", "ganq_profile_enable", "ganq_profile_read"]
+           "ganq_quantize_layer", "ganq_outlier_split", "ganq_packed_row_bytes", "ganq_pack_layer",
+           "ganq_lut_gemv", "ganq_profile_enable", "ganq_profile_read"]
 
 KERNEL_CLASSES = ["hessian", "cholesky", "init", "gemm_wh", "update_s", "t_prep", "t_pad", "t_accum",
-                  "t_solve", "loss", "outlier"]
+                  "t_solve", "loss", "outlier", "pack", "lut_gemv"]
 
 
 class GanqOptions(ctypes.Structure):
@@ -74,6 +75,12 @@ def load_library():
     lib.ganq_cholesky.restype = ci
     lib.ganq_init_codebooks.argtypes = [vp, vp, ci, i64, i64, i64, ci, ci, vp]
     lib.ganq_init_codebooks.restype = ci
+    lib.ganq_packed_row_bytes.argtypes = [i64, ci]
+    lib.ganq_packed_row_bytes.restype = i64
+    lib.ganq_pack_layer.argtypes = [vp, vp, i64, i64, i64, vp, ci, vp, i64, vp]
+    lib.ganq_pack_layer.restype = ci
+    lib.ganq_lut_gemv.argtypes = [vp, vp, i64, vp, ci, i64, i64, vp, vp, vp, vp, vp]
+    lib.ganq_lut_gemv.restype = ci
     lib.ganq_update_S.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, ci, vp, i64, vp, i64]
     lib.ganq_update_S.restype = ci
     lib.ganq_update_T.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, i64, ci, ci, vp, vp]
@@ -267,6 +274,35 @@ class Context:
             break
         self._check(st)
         return Wd, row_ptr, col[:nnz.value], val[:nnz.value]
+
+    def pack_layer(self, Q, T, nbits):
+        """Stored form of a quantized layer: (packed uint8 (m, row bytes), lut float16 (m, 2^N))."""
+        m, n = Q.shape
+        rb = int(self.lib.ganq_packed_row_bytes(n, nbits))
+        if rb <= 0:
+            raise ValueError("nbits must be 1..4 and n positive")
+        packed = torch.empty(m, rb, dtype=torch.uint8, device=Q.device)
+        lut = torch.empty(m, 1 << nbits, dtype=torch.float16, device=Q.device)
+        if T.dtype != torch.float32 or not T.is_contiguous() or tuple(T.shape) != (m, 1 << nbits):
+            raise ValueError("T must be a contiguous float32 (m, 2^N) tensor")
+        self._check(self.lib.ganq_pack_layer(self.handle, _ptr(Q), m, n, _rowmajor(Q, "Q"), _ptr(T), nbits,
+                                             _ptr(packed), rb, _ptr(lut)))
+        return packed, lut
+
+    def lut_gemv(self, packed, lut, nbits, n, x, y=None, outliers=None):
+        """y = W~ x (+ W_sparse x) from the stored form; x float16 (n,), y float32 (m,).
+        outliers = (row_ptr int64, col_idx int32, values float32) or None.  Asynchronous."""
+        m = packed.shape[0]
+        if x.dtype != torch.float16 or x.dim() != 1 or x.shape[0] != n or not x.is_contiguous():
+            raise ValueError("x must be a contiguous float16 vector of n entries")
+        if lut.dtype != torch.float16 or not lut.is_contiguous() or tuple(lut.shape) != (m, 1 << nbits):
+            raise ValueError("lut must be a contiguous float16 (m, 2^N) tensor")
+        if y is None:
+            y = torch.empty(m, dtype=torch.float32, device=x.device)
+        rp, ci_, va = outliers if outliers is not None else (None, None, None)
+        self._check(self.lib.ganq_lut_gemv(self.handle, _ptr(packed), _rowmajor(packed, "packed"), _ptr(lut),
+                                           nbits, m, n, _ptr(x), _ptr(y), _ptr(rp), _ptr(ci_), _ptr(va)))
+        return y
 
     def quantize_layer(self, W, H, nbits, iters, T=None, L=None, precond=PRECOND_NONE, lam=0.0,
                        init=INIT_QUANTILE_MID, empty=EMPTY_ZERO, Q=None, history=False):

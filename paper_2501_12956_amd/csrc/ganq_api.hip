@@ -250,6 +250,56 @@ ganq_status ganq_outlier_split(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype,
   return GANQ_OK;
 }
 
+int64_t ganq_packed_row_bytes(int64_t n, int nbits) {
+  if (n <= 0 || nbits < 1 || nbits > 4) return 0;
+  return packed_row_bytes(n, nbits);
+}
+
+ganq_status ganq_pack_layer(ganq_ctx* ctx, const uint8_t* Q, int64_t m, int64_t n, int64_t ldq,
+                            const float* T, int nbits, uint8_t* packed, int64_t ldp, uint16_t* lut) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  GANQ_REQUIRE(ctx, nbits >= 1 && nbits <= 4, "nbits must be 1..4");
+  GANQ_REQUIRE(ctx, m > 0 && n > 0, "m and n must be positive");
+  GANQ_REQUIRE(ctx, Q != nullptr && ldq >= n, "Q / ldq");
+  GANQ_REQUIRE(ctx, T != nullptr && lut != nullptr, "T / lut");
+  GANQ_REQUIRE(ctx, packed != nullptr && ((uintptr_t)packed % 16) == 0, "packed must be 16-byte aligned");
+  GANQ_REQUIRE(ctx, ldp % 16 == 0 && ldp >= packed_row_bytes(n, nbits), "ldp");
+  if (m > kMaxDim) return fail(ctx, GANQ_ERR_UNSUPPORTED, "m must not exceed 65535");
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  {
+    ProfScope prof(ctx, GANQ_K_PACK);
+    GANQ_HIP(ctx, launch_pack_layer(ctx->stream, Q, m, n, ldq, T, nbits, packed, ldp, lut));
+  }
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
+ganq_status ganq_lut_gemv(ganq_ctx* ctx, const uint8_t* packed, int64_t ldp, const uint16_t* lut,
+                          int nbits, int64_t m, int64_t n, const void* x, float* y,
+                          const int64_t* row_ptr, const int32_t* col_idx, const float* values) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  GANQ_REQUIRE(ctx, nbits >= 1 && nbits <= 4, "nbits must be 1..4");
+  GANQ_REQUIRE(ctx, m > 0 && n > 0, "m and n must be positive");
+  GANQ_REQUIRE(ctx, packed != nullptr && ((uintptr_t)packed % 16) == 0, "packed must be 16-byte aligned");
+  GANQ_REQUIRE(ctx, ldp % 16 == 0 && ldp >= packed_row_bytes(n, nbits), "ldp");
+  GANQ_REQUIRE(ctx, lut != nullptr && x != nullptr && y != nullptr, "lut / x / y");
+  GANQ_REQUIRE(ctx, ((uintptr_t)x % 2) == 0, "x must be 2-byte aligned");
+  const bool sparse = row_ptr != nullptr;
+  GANQ_REQUIRE(ctx, sparse == (col_idx != nullptr) && sparse == (values != nullptr),
+               "row_ptr, col_idx and values go together");
+  if (m > (int64_t)kMaxDim * 16) return fail(ctx, GANQ_ERR_UNSUPPORTED, "m must not exceed 1048560");
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  {
+    ProfScope prof(ctx, GANQ_K_LUT_GEMV);
+    GANQ_HIP(ctx, launch_lut_gemv(ctx->stream, packed, ldp, lut, nbits, m, n, (const _Float16*)x, y, row_ptr,
+                                  col_idx, values));
+  }
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
 ganq_status ganq_profile_enable(ganq_ctx* ctx, int on) {
   if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
   if (ctx->device_ready && !ctx->prof_pending.empty()) {

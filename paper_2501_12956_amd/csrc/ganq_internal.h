@@ -73,6 +73,12 @@ hipError_t launch_gemm_split(hipStream_t s, int64_t M, int64_t N, int64_t K, con
 hipError_t launch_outlier_split(hipStream_t s, const void* W, int w_is_f16, int64_t m, int64_t n, int64_t ldw,
                                 int lower, int upper, float* Wd, int64_t ldd, int64_t* row_ptr,
                                 int32_t* col_idx, float* values, int64_t capacity, void* scratch);
+int64_t packed_row_bytes(int64_t n, int nbits);
+hipError_t launch_pack_layer(hipStream_t s, const uint8_t* Q, int64_t m, int64_t n, int64_t ldq,
+                             const float* T, int nbits, uint8_t* packed, int64_t ldp, uint16_t* lut);
+hipError_t launch_lut_gemv(hipStream_t s, const uint8_t* packed, int64_t ldp, const uint16_t* lut, int nbits,
+                           int64_t m, int64_t n, const _Float16* x, float* y, const int64_t* row_ptr,
+                           const int32_t* col_idx, const float* values);
 
 // ---- kernel launchers (all enqueue on `s`, return the HIP error of the launch) ----
 
