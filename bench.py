@@ -9,6 +9,11 @@ alternations of S-update and T-update (Algorithm 1), and one evaluation of the
 objective.  The headline workload is the LLaMA-7B q_proj-shaped layer at 4 bits
 (4096 x 4096, X 4096 x 262144 fp16, 10 alternations).
 
+    python bench.py --decode [--config c5] [--nbits 4] [--steps K] [--warmup W]
+
+times the deployment-side look-up-table product (batch-1 decoding from the stored form) instead;
+see decode_main().
+
 Prints ONE JSON line with the seconds per layer, a per-kernel-class breakdown
 measured with HIP events on the library's stream inside the timed region, the
 roofline figure of the dominant kernel, and the float64 CPU oracle timed on a
@@ -109,6 +114,99 @@ def cpu_baseline(cfg, X_dev, W_dev, rows=256, tokens=16384):
     }
 
 
+def decode_main(args):
+    """The look-up-table product y = W~ x from the stored form (N-bit codes + fp16 tables), timed over
+    enough distinct layers of the given shape that the codes stream from HBM rather than from a cache
+    (at least 768 MB in total).  One step = one product per layer copy; the line reports microseconds
+    per product and the stored bytes per product over the kernel's average launch time against the HBM
+    peak.  cpu_baseline: the float64 definition on a sample of rows."""
+    import numpy as np
+    import torch
+    from paper_2501_12956_amd import binding, synth
+
+    cfg = synth.CONFIGS[args.config]
+    m, n, nbits = cfg.m, cfg.n, args.nbits
+    C = 1 << nbits
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    ctx = binding.Context(0)
+    stored = m * n * nbits / 8 + m * C * 2
+    copies = max(2, int(-(-768e6 // stored)))
+    g = torch.Generator(device=dev).manual_seed(1)
+    layers = []
+    for _ in range(copies):
+        Q = torch.randint(0, C, (m, n), dtype=torch.uint8, device=dev, generator=g)
+        T = (torch.randn(m, C, device=dev, generator=g) * 0.02).sort(dim=1).values.contiguous()
+        layers.append(ctx.pack_layer(Q, T, nbits))
+    x = torch.randn(n, device=dev, generator=g).half()
+    y = torch.empty(m, dtype=torch.float32, device=dev)
+
+    def step():
+        for packed, lut in layers:
+            ctx.lut_gemv(packed, lut, nbits, n, x, y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    # a second pass with an event pair around every launch gives the kernel's own duration (the
+    # events cost host time per call, so this pass is not the one that is timed as a whole)
+    ctx.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms, cnt = ctx.profile_read()["lut_gemv"]
+    ctx.profile_enable(False)
+    avg_ms = ms / cnt
+    us = 1e6 * elapsed / (args.steps * copies)
+    algo_bytes = stored + 2 * n + 4 * m
+    achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
+
+    # the same product on fp16 weights by the vendor library, for context (Table 6 compares with FP16)
+    Wd = [torch.randn(m, n, device=dev, dtype=torch.float16) for _ in range(max(2, int(768e6 // (2 * m * n))))]
+    for Wk in Wd:
+        torch.mv(Wk, x)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        for Wk in Wd:
+            torch.mv(Wk, x)
+    torch.cuda.synchronize()
+    dense_us = 1e6 * (time.perf_counter() - t1) / (args.steps * len(Wd))
+
+    out = {
+        "metric": "microseconds per look-up-table product (batch 1) of one stored layer",
+        "value": us, "unit": "us/product", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 x f16 -> f32", "data": "synthetic",
+        "config": {"workload": "%s-shaped layer %dx%d stored at %d bits + fp16 tables, x fp16, %d distinct "
+                               "layers per step" % (cfg.name, m, n, nbits, copies)},
+        "roofline": {"kernel": "lut_gemv", "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                     "avg_launch_ms": avg_ms},
+        "fp16_dense_mv_us": dense_us,
+    }
+    if not args.no_cpu_baseline:
+        from oracle import ganq_ref as ref
+        rows = 256
+        packed, lut = layers[0]
+        Qs = torch.from_numpy(ref.unpack_codes(packed[:rows].cpu().numpy()[:, :ref.packed_row_bytes(n, nbits)],
+                                               n, nbits))
+        t2 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t2 < 10.0:
+            ref.lut_matvec(lut[:rows].cpu().numpy(), Qs.numpy(), x.cpu().numpy())
+            reps += 1
+        dt = (time.perf_counter() - t2) / reps
+        out["cpu_baseline"] = {"value": 1e6 * dt * m / rows, "unit": "us/product", "cores": 1, "kind": "oracle",
+                               "sample": "%d of %d rows, scaled by rows" % (rows, m)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,11 +217,17 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region: under "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE its reading gives the scale of the counter")
+    ap.add_argument("--decode", action="store_true",
+                    help="time the deployment-side look-up-table product instead of the solver")
+    ap.add_argument("--nbits", type=int, default=4, help="--decode only: bits per stored code")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the solver has no multi-GPU path); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+
+    if args.decode:
+        return decode_main(args)
 
     import torch
     from paper_2501_12956_amd import binding, synth

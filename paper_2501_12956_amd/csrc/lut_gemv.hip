@@ -9,16 +9,22 @@
 // covers 2048 columns ("segment") per fetch and a row needs no padding beyond the
 // last group of 32.
 //
-// The product is bound by the stream of codes from HBM; what has to keep up with
-// it is the table look-up.  Looking codes up in pairs halves the LDS operations:
-// the workgroup first expands each of its 16 rows' tables into a table of all 4^N
-// ordered pairs (T[a], T[b]) as packed fp16 pairs, indexed by the 2N bits of two
-// adjacent codes, so one 4-byte LDS read feeds one v_dot2_f32_f16 against the
-// matching pair of activations (fp32 accumulation).  A workgroup owns 16 whole
-// rows; its 8 wavefronts are arranged as (row group) x (segment lane), the segment
-// lanes striding over the segments of a row.  Per-lane partial sums are reduced
-// once per row at the end, the segment lanes' sums are added in a fixed order
-// through LDS: results are bit-reproducible.
+// The codes stream from HBM once; what has to keep up with them is the table
+// look-up, one per weight.  The 16 rows' tables sit in LDS with one entry per bank
+// (fp16 in the low half of a 4-byte word, rows 64 bytes apart): a look-up
+// instruction of a wavefront reads one row's table, so its at most 16 distinct
+// addresses fall into 16 distinct banks and it never conflicts (a table of code
+// pairs would halve the number of LDS reads, but its 4^N words collide: measured
+// slower at N = 4).  The byte offset of a code's entry is cut out of the code word
+// in 1.5 operations per code (for N = 1, 2, 4: masked copies of the whole word, then
+// one byte extraction per code), and the entry meets its activation in a mixed
+// fp16 x fp16 -> fp32 fused multiply-add, which is exact in the product.  Look-ups
+// run one batch ahead of the multiply-adds.  A workgroup owns 16 whole rows; its 8
+// wavefronts are arranged as (row group) x (segment lane), the segment lanes
+// striding over the segments of a row.  Per-lane partial sums are reduced once per
+// row at the end, the segment lanes' sums are added in a fixed order through LDS:
+// results are bit-reproducible.  On the large layers the kernel is bound by LDS
+// instruction issue and vector ALU work per code, not by HBM.
 #include "ganq_internal.h"
 
 namespace ganq {
@@ -36,43 +42,92 @@ __device__ inline float wave_sum(float v) {
   return v;
 }
 
-// The 2N bits of code pair p (codes 2p and 2p + 1) of a 32-code group held in d[0..N).
+// One 32-code group (N words) from global memory, as one vector load.
 template <int N>
-__device__ inline uint32_t pair_index(const uint32_t (&d)[N], int p) {
-  const int bit = 2 * N * p;
-  const int w = bit >> 5, sh = bit & 31;
-  uint32_t v = d[w] >> sh;
-  if (sh + 2 * N > 32) v |= d[(w + 1 < N) ? w + 1 : w] << (32 - sh);   // straddles two words (N = 3)
-  return v & ((1u << (2 * N)) - 1u);
+__device__ inline void load_group(const uint32_t* __restrict__ p, uint32_t (&d)[N]) {
+  if constexpr (N == 4) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+  } else if constexpr (N == 3) {
+    struct __attribute__((packed, aligned(4))) U3 { uint32_t a, b, c; };
+    const U3 v = *reinterpret_cast<const U3*>(p);
+    d[0] = v.a; d[1] = v.b; d[2] = v.c;
+  } else if constexpr (N == 2) {
+    const uint2 v = *reinterpret_cast<const uint2*>(p);
+    d[0] = v.x; d[1] = v.y;
+  } else {
+    d[0] = *p;
+  }
 }
+
+// Byte offsets (4 * code) of the 32 codes of a group within their row's table.
+// N = 1, 2, 4: a code never straddles a byte, so the word is masked once per position of a code
+// within a byte (all four bytes at a time, 2 operations per 4 codes) and each code then costs
+// one byte extraction.  The empty asm keeps the compiler from folding the two steps back into
+// a shift and a mask per code.  N = 3: shift and mask per code, a funnel shift where a code
+// straddles two words.
+template <int N>
+struct GroupOffsets {
+  static constexpr int PB = (N == 3) ? 1 : 8 / N;     // code positions within a byte
+  uint32_t mk[N][PB];
+  uint32_t raw[N];
+  __device__ inline explicit GroupOffsets(const uint32_t (&d)[N]) {
+    constexpr uint32_t mask = ((1u << N) - 1u) << 2;
+#pragma unroll
+    for (int w = 0; w < N; ++w) {
+      raw[w] = d[w];
+      if constexpr (N != 3) {
+#pragma unroll
+        for (int ps = 0; ps < PB; ++ps) {
+          uint32_t v = ((N * ps < 2) ? (d[w] << (2 - N * ps)) : (d[w] >> (N * ps - 2))) & (mask * 0x01010101u);
+          asm("" : "+v"(v));
+          mk[w][ps] = v;
+        }
+      }
+    }
+  }
+  __device__ inline uint32_t at(int j) const {
+    constexpr uint32_t mask = ((1u << N) - 1u) << 2;
+    const int bit = N * j;
+    const int w = bit >> 5, sh = bit & 31;
+    if constexpr (N == 3) {
+      if (sh + N > 32) {
+        const uint32_t v = __builtin_amdgcn_alignbit(raw[(w + 1 < N) ? w + 1 : w], raw[w], sh);
+        return (v << 2) & mask;
+      }
+      if (sh < 2) return (raw[w] << (2 - sh)) & mask;
+      return (raw[w] >> (sh - 2)) & mask;
+    } else {
+      return (mk[w][(sh & 7) / N] >> (8 * (sh >> 3))) & 0xffu;
+    }
+  }
+};
 
 // SW = segment lanes (1, 2, 4 or 8 wavefronts side by side on one row); the other
 // 8 / SW wavefronts take different rows, so every wavefront owns 2 SW of the 16 rows.
 template <int N, int SW>
-__global__ __launch_bounds__(64 * GNW) void lut_gemv_kernel(
+__global__ __launch_bounds__(64 * GNW, 4) void lut_gemv_kernel(
     const uint8_t* __restrict__ packed, int64_t ldp, const uint16_t* __restrict__ lut, int64_t m,
     int64_t n, const _Float16* __restrict__ x, float* __restrict__ y,
     const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
     const float* __restrict__ values) {
-  constexpr int C = 1 << N, PT = C * C;
+  constexpr int C = 1 << N;
   constexpr int RG = GNW / SW;      // row groups
   constexpr int RPW = GR / RG;      // rows per wavefront
-  __shared__ uint32_t tab[GR][PT];
+  __shared__ __attribute__((aligned(16))) uint32_t tab[GR][16];   // one entry per bank: fp16 in the low half
   __shared__ float part[SW][GR];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int sl = wave % SW, g = wave / SW;
+  const int sl = wave % SW, g = (RG == 1) ? 0 : wave / SW;
   const int64_t row0 = (int64_t)blockIdx.x * GR;
 
-  // pair tables of the 16 rows: entry (b << N | a) = (T[a], T[b]) as two fp16
-  for (int e = tid; e < GR * PT; e += 64 * GNW) {
-    const int r = e / PT, idx = e % PT;
-    const int64_t row = row0 + r;
-    uint32_t v = 0;
-    if (row < m) v = (uint32_t)lut[row * C + (idx & (C - 1))] | ((uint32_t)lut[row * C + (idx >> N)] << 16);
-    tab[r][idx] = v;
+  // the 16 rows' tables
+  if (tid < GR * C) {
+    const int r = tid / C, c = tid % C;
+    tab[r][c] = (row0 + r < m) ? (uint32_t)lut[(row0 + r) * C + c] : 0u;
   }
+  const uint32_t gbase = (uint32_t)g * 64u;       // this wavefront's rows are g, g + RG, ...
   __syncthreads();
 
   float acc[RPW];
@@ -100,28 +155,55 @@ __global__ __launch_bounds__(64 * GNW) void lut_gemv_kernel(
         xr[u] = lo | (hi << 16);
       }
     }
-    // the code groups of this wavefront's rows, all fetched before any is used
+    // the code groups of this wavefront's rows, all fetched before any is used; a lane whose
+    // group lies outside the matrix fetches group 0 of row 0 instead and discards it
     uint32_t q[RPW][N];
 #pragma unroll
     for (int k = 0; k < RPW; ++k) {
       const int64_t row = row0 + g + RG * k;
       const bool ok = row < m && col0 < n;
-      const uint32_t* src =
-          reinterpret_cast<const uint32_t*>(packed + row * ldp) + (seg * 64 + lane) * N;
+      const uint32_t* src = reinterpret_cast<const uint32_t*>(packed + (ok ? row : 0) * ldp) +
+                            (ok ? (seg * 64 + lane) * N : 0);
+      load_group<N>(src, q[k]);
 #pragma unroll
-      for (int w = 0; w < N; ++w) q[k][w] = ok ? src[w] : 0u;
+      for (int w = 0; w < N; ++w) q[k][w] = ok ? q[k][w] : 0u;
     }
+    // Look-ups in batches (4 or 8 codes of two rows): the reads of the next batch are issued
+    // before the previous batch is multiplied, and the scheduling barriers keep it that way
+    // (left alone, the compiler waits for every single read).  The two rows' multiply-adds
+    // alternate, so consecutive instructions do not depend on each other.
+    constexpr int LB = (RPW * N >= 64) ? 4 : 8;     // codes per row and batch (register budget)
+    constexpr int BPR = 32 / LB;                    // batches per pair of rows
+    constexpr int NB = (RPW / 2) * BPR;
+    _Float16 ev[2][2 * LB];
+    auto lookup = [&](int bt, _Float16 (&e)[2 * LB]) {
+      const int kp = bt / BPR, h = bt % BPR;
 #pragma unroll
-    for (int k = 0; k < RPW; ++k) {
-      const uint32_t* t = tab[g + RG * k];
-      float a = acc[k];
+      for (int rr = 0; rr < 2; ++rr) {
+        const int k = 2 * kp + rr;
+        const char* t = reinterpret_cast<const char*>(tab[RG * k]);
+        const GroupOffsets<N> off(q[k]);
 #pragma unroll
-      for (int p = 0; p < 16; ++p) {
-        const uint32_t e = t[pair_index<N>(q[k], p)];
-        a = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, e), __builtin_bit_cast(half2v, xr[p]), a,
-                                   false);
+        for (int j = 0; j < LB; ++j)
+          e[LB * rr + j] = *reinterpret_cast<const _Float16*>(t + (off.at(LB * h + j) | gbase));
       }
-      acc[k] = a;
+    };
+    lookup(0, ev[0]);
+#pragma unroll
+    for (int bt = 0; bt < NB; ++bt) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (bt + 1 < NB) lookup(bt + 1, ev[(bt + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
+      const int kp = bt / BPR, h = bt % BPR;
+      float a0 = acc[2 * kp], a1 = acc[2 * kp + 1];
+#pragma unroll
+      for (int j = 0; j < LB; ++j) {
+        const half2v xx = __builtin_bit_cast(half2v, xr[(LB * h + j) >> 1]);
+        a0 = fmaf((float)ev[bt & 1][j], (float)xx[j & 1], a0);
+        a1 = fmaf((float)ev[bt & 1][LB + j], (float)xx[j & 1], a1);
+      }
+      acc[2 * kp] = a0;
+      acc[2 * kp + 1] = a1;
     }
   }
 
@@ -198,13 +280,21 @@ hipError_t launch_gemv_n(hipStream_t s, const uint8_t* packed, int64_t ldp, cons
                          const int32_t* col_idx, const float* values) {
   const int64_t nseg = ceil_div(n, GSEG);
   const dim3 grid((unsigned)ceil_div(m, GR)), block(64 * GNW);
-  if (nseg >= 8)
+  // segment lanes: the widest arrangement among those that leave the fewest lanes idle in the
+  // last round over the segments
+  int sw = 1;
+  int64_t best = nseg;                       // slots used with one lane: no idle slot
+  for (int c = 2; c <= 8; c *= 2) {
+    const int64_t slots = ceil_div(nseg, c) * c;
+    if (slots <= best) { best = slots; sw = c; }
+  }
+  if (sw == 8)
     hipLaunchKernelGGL((lut_gemv_kernel<N, 8>), grid, block, 0, s, packed, ldp, lut, m, n, x, y, row_ptr,
                        col_idx, values);
-  else if (nseg >= 4)
+  else if (sw == 4)
     hipLaunchKernelGGL((lut_gemv_kernel<N, 4>), grid, block, 0, s, packed, ldp, lut, m, n, x, y, row_ptr,
                        col_idx, values);
-  else if (nseg >= 2)
+  else if (sw == 2)
     hipLaunchKernelGGL((lut_gemv_kernel<N, 2>), grid, block, 0, s, packed, ldp, lut, m, n, x, y, row_ptr,
                        col_idx, values);
   else
