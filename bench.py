@@ -148,21 +148,19 @@ def decode_main(args):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # The launches are back to back on the context's stream (torch's current one), so one HIP event
+    # pair around the region gives the kernel's average duration; a pair around each 10-40 us launch
+    # would add to it.
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev0.record()
     for _ in range(args.steps):
         step()
+    ev1.record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    # a second pass with an event pair around every launch gives the kernel's own duration (the
-    # events cost host time per call, so this pass is not the one that is timed as a whole)
-    ctx.profile_enable(True)
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms, cnt = ctx.profile_read()["lut_gemv"]
-    ctx.profile_enable(False)
-    avg_ms = ms / cnt
     us = 1e6 * elapsed / (args.steps * copies)
+    avg_ms = ev0.elapsed_time(ev1) / (args.steps * copies)
     algo_bytes = stored + 2 * n + 4 * m
     achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
 

@@ -258,9 +258,23 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ Q
   uint32_t out[N];
 #pragma unroll
   for (int w = 0; w < N; ++w) out[w] = 0u;
+  uint32_t in[8];       // the 32 codes, four per word
+  if (grp * 32 + 32 <= n && ((uintptr_t)src & 15) == 0) {
+    const uint4 a = reinterpret_cast<const uint4*>(src)[0], b = reinterpret_cast<const uint4*>(src)[1];
+    in[0] = a.x; in[1] = a.y; in[2] = a.z; in[3] = a.w;
+    in[4] = b.x; in[5] = b.y; in[6] = b.z; in[7] = b.w;
+  } else {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      in[u] = 0u;
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        if (grp * 32 + 4 * u + b < n) in[u] |= (uint32_t)src[4 * u + b] << (8 * b);
+    }
+  }
 #pragma unroll
   for (int j = 0; j < 32; ++j) {
-    const uint32_t c = (grp * 32 + j < n) ? (uint32_t)(src[j] & (C - 1)) : 0u;
+    const uint32_t c = (in[j >> 2] >> (8 * (j & 3))) & (C - 1);
     const int bit = N * j, w = bit >> 5, sh = bit & 31;
     out[w] |= c << sh;
     if (sh + N > 32) out[w + 1 < N ? w + 1 : w] |= c >> (32 - sh);
