@@ -114,6 +114,11 @@ def cpu_baseline(cfg, X_dev, W_dev, rows=256, tokens=16384):
     }
 
 
+# HBM bytes per look-up-table product (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, KiB per dispatch, from
+# profiles/decode_c5_kernel_stats.txt); other shapes report null.
+TRAFFIC_DECODE_BYTES = {("c5", 4): (57757.9 * 2.000 + 32.0) * 1024}
+
+
 def decode_main(args):
     """The look-up-table product y = W~ x from the stored form (N-bit codes + fp16 tables), timed over
     enough distinct layers of the given shape that the codes stream from HBM rather than from a cache
@@ -184,7 +189,8 @@ def decode_main(args):
         "config": {"workload": "%s-shaped layer %dx%d stored at %d bits + fp16 tables, x fp16, %d distinct "
                                "layers per step" % (cfg.name, m, n, nbits, copies)},
         "roofline": {"kernel": "lut_gemv", "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS,
-                     "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
+                     "traffic": TRAFFIC_DECODE_BYTES.get((cfg.name, nbits)),
                      "avg_launch_ms": avg_ms},
         "fp16_dense_mv_us": dense_us,
     }
