@@ -10,15 +10,17 @@
 // last group of 32.
 //
 // The codes stream from HBM once; what has to keep up with them is the table
-// look-up, one per weight.  The 16 rows' tables sit in LDS with one entry per bank
+// look-up.  The 16 rows' tables sit in LDS.  At N = 4 a table has one entry per bank
 // (fp16 in the low half of a 4-byte word, rows 64 bytes apart): a look-up
 // instruction of a wavefront reads one row's table, so its at most 16 distinct
-// addresses fall into 16 distinct banks and it never conflicts (a table of code
-// pairs would halve the number of LDS reads, but its 4^N words collide: measured
-// slower at N = 4).  The byte offset of a code's entry is cut out of the code word
-// in 1.5 operations per code (for N = 1, 2, 4: masked copies of the whole word, then
-// one byte extraction per code), and the entry meets its activation in a mixed
-// fp16 x fp16 -> fp32 fused multiply-add, which is exact in the product.  Look-ups
+// addresses fall into 16 distinct banks and it never conflicts; the entry meets its
+// activation in a mixed fp16 x fp16 -> fp32 fused multiply-add, exact in the
+// product.  At N <= 3 two adjacent codes are looked up at once in a table of all
+// 4^N ordered pairs (at most 64 words, two per bank) and meet their two activations
+// in one v_dot2_f32_f16: half the LDS reads and half the arithmetic per code (at
+// N = 4 the 256 words of such a table collide in the banks: measured slower).  The
+// byte offset of an entry is cut out of the code words with masked copies of a whole
+// word and one byte extraction per look-up where fields do not straddle bytes.  Look-ups
 // run one batch ahead of the multiply-adds.  A workgroup owns 16 whole rows; its 8
 // wavefronts are arranged as (row group) x (segment lane), the segment lanes
 // striding over the segments of a row.  Per-lane partial sums are reduced once per
@@ -60,26 +62,28 @@ __device__ inline void load_group(const uint32_t* __restrict__ p, uint32_t (&d)[
   }
 }
 
-// Byte offsets (4 * code) of the 32 codes of a group within their row's table.
-// N = 1, 2, 4: a code never straddles a byte, so the word is masked once per position of a code
-// within a byte (all four bytes at a time, 2 operations per 4 codes) and each code then costs
-// one byte extraction.  The empty asm keeps the compiler from folding the two steps back into
-// a shift and a mask per code.  N = 3: shift and mask per code, a funnel shift where a code
-// straddles two words.
-template <int N>
-struct GroupOffsets {
-  static constexpr int PB = (N == 3) ? 1 : 8 / N;     // code positions within a byte
-  uint32_t mk[N][PB];
-  uint32_t raw[N];
-  __device__ inline explicit GroupOffsets(const uint32_t (&d)[N]) {
-    constexpr uint32_t mask = ((1u << N) - 1u) << 2;
+// Byte offsets (4 * field value) of the F-bit fields of a 32-code group held in NW words: a
+// field is one code (F = N) or two adjacent codes (F = 2 N).
+// F = 1, 2, 4: a field never straddles a byte, so the word is masked once per position of a
+// field within a byte (all four bytes at a time, 2 operations per 4 fields) and each field then
+// costs one byte extraction; the empty asm keeps the compiler from folding the two steps back
+// into a shift and a mask per field.  F = 6: shift and mask per field, a funnel shift where a
+// field straddles two words.
+template <int F, int NW>
+struct FieldOffsets {
+  static constexpr bool BYTEWISE = (8 % F) == 0;
+  static constexpr int PB = BYTEWISE ? 8 / F : 1;      // field positions within a byte
+  static constexpr uint32_t MASK = ((1u << F) - 1u) << 2;
+  uint32_t mk[NW][PB];
+  uint32_t raw[NW];
+  __device__ inline explicit FieldOffsets(const uint32_t (&d)[NW]) {
 #pragma unroll
-    for (int w = 0; w < N; ++w) {
+    for (int w = 0; w < NW; ++w) {
       raw[w] = d[w];
-      if constexpr (N != 3) {
+      if constexpr (BYTEWISE) {
 #pragma unroll
         for (int ps = 0; ps < PB; ++ps) {
-          uint32_t v = ((N * ps < 2) ? (d[w] << (2 - N * ps)) : (d[w] >> (N * ps - 2))) & (mask * 0x01010101u);
+          uint32_t v = ((F * ps < 2) ? (d[w] << (2 - F * ps)) : (d[w] >> (F * ps - 2))) & (MASK * 0x01010101u);
           asm("" : "+v"(v));
           mk[w][ps] = v;
         }
@@ -87,18 +91,17 @@ struct GroupOffsets {
     }
   }
   __device__ inline uint32_t at(int j) const {
-    constexpr uint32_t mask = ((1u << N) - 1u) << 2;
-    const int bit = N * j;
+    const int bit = F * j;
     const int w = bit >> 5, sh = bit & 31;
-    if constexpr (N == 3) {
-      if (sh + N > 32) {
-        const uint32_t v = __builtin_amdgcn_alignbit(raw[(w + 1 < N) ? w + 1 : w], raw[w], sh);
-        return (v << 2) & mask;
-      }
-      if (sh < 2) return (raw[w] << (2 - sh)) & mask;
-      return (raw[w] >> (sh - 2)) & mask;
+    if constexpr (BYTEWISE) {
+      return (mk[w][(sh & 7) / F] >> (8 * (sh >> 3))) & 0xffu;
     } else {
-      return (mk[w][(sh & 7) / N] >> (8 * (sh >> 3))) & 0xffu;
+      if (sh + F > 32) {
+        const uint32_t v = __builtin_amdgcn_alignbit(raw[(w + 1 < NW) ? w + 1 : w], raw[w], sh);
+        return (v << 2) & MASK;
+      }
+      if (sh < 2) return (raw[w] << (2 - sh)) & MASK;
+      return (raw[w] >> (sh - 2)) & MASK;
     }
   }
 };
@@ -114,7 +117,14 @@ __global__ __launch_bounds__(64 * GNW, 4) void lut_gemv_kernel(
   constexpr int C = 1 << N;
   constexpr int RG = GNW / SW;      // row groups
   constexpr int RPW = GR / RG;      // rows per wavefront
-  __shared__ __attribute__((aligned(16))) uint32_t tab[GR][16];   // one entry per bank: fp16 in the low half
+  // N <= 3: codes are looked up in pairs, in a table of all 4^N ordered pairs (T[a], T[b]) as
+  // packed fp16 pairs (at most 64 words per row: two per bank); N = 4: one by one (256 words
+  // would collide in the banks), the entry in the low half of a word.
+  constexpr bool PAIR = N <= 3;
+  constexpr int F = PAIR ? 2 * N : N;          // bits per look-up
+  constexpr int TW = 1 << F;                   // table words per row
+  constexpr int LPG = 32 * N / F;              // look-ups per 32-code group
+  __shared__ __attribute__((aligned(16))) uint32_t tab[GR][TW];
   __shared__ float part[SW][GR];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -123,11 +133,16 @@ __global__ __launch_bounds__(64 * GNW, 4) void lut_gemv_kernel(
   const int64_t row0 = (int64_t)blockIdx.x * GR;
 
   // the 16 rows' tables
-  if (tid < GR * C) {
-    const int r = tid / C, c = tid % C;
-    tab[r][c] = (row0 + r < m) ? (uint32_t)lut[(row0 + r) * C + c] : 0u;
+  for (int e = tid; e < GR * TW; e += 64 * GNW) {
+    const int r = e / TW, idx = e % TW;
+    uint32_t v = 0u;
+    if (row0 + r < m) {
+      const uint16_t* lr = lut + (row0 + r) * C;
+      v = PAIR ? ((uint32_t)lr[idx & (C - 1)] | ((uint32_t)lr[idx >> N] << 16)) : (uint32_t)lr[idx];
+    }
+    tab[r][idx] = v;
   }
-  const uint32_t gbase = (uint32_t)g * 64u;       // this wavefront's rows are g, g + RG, ...
+  const uint32_t gbase = (uint32_t)g * (TW * 4u);   // this wavefront's rows are g, g + RG, ...
   __syncthreads();
 
   float acc[RPW];
@@ -168,24 +183,29 @@ __global__ __launch_bounds__(64 * GNW, 4) void lut_gemv_kernel(
 #pragma unroll
       for (int w = 0; w < N; ++w) q[k][w] = ok ? q[k][w] : 0u;
     }
-    // Look-ups in batches (4 or 8 codes of two rows): the reads of the next batch are issued
+    // Look-ups in batches (LB per row, two rows): the reads of the next batch are issued
     // before the previous batch is multiplied, and the scheduling barriers keep it that way
     // (left alone, the compiler waits for every single read).  The two rows' multiply-adds
     // alternate, so consecutive instructions do not depend on each other.
-    constexpr int LB = (RPW * N >= 64) ? 4 : 8;     // codes per row and batch (register budget)
-    constexpr int BPR = 32 / LB;                    // batches per pair of rows
+    constexpr int LB = (RPW * N >= 64) ? 4 : 8;     // look-ups per row and batch (register budget)
+    constexpr int BPR = LPG / LB;                   // batches per pair of rows
     constexpr int NB = (RPW / 2) * BPR;
-    _Float16 ev[2][2 * LB];
-    auto lookup = [&](int bt, _Float16 (&e)[2 * LB]) {
+    uint32_t ev[2][2 * LB];
+    auto lookup = [&](int bt, uint32_t (&e)[2 * LB]) {
       const int kp = bt / BPR, h = bt % BPR;
 #pragma unroll
       for (int rr = 0; rr < 2; ++rr) {
         const int k = 2 * kp + rr;
         const char* t = reinterpret_cast<const char*>(tab[RG * k]);
-        const GroupOffsets<N> off(q[k]);
+        const FieldOffsets<F, N> off(q[k]);
 #pragma unroll
-        for (int j = 0; j < LB; ++j)
-          e[LB * rr + j] = *reinterpret_cast<const _Float16*>(t + (off.at(LB * h + j) | gbase));
+        for (int j = 0; j < LB; ++j) {
+          const uint32_t o = off.at(LB * h + j) | gbase;
+          if constexpr (PAIR)
+            e[LB * rr + j] = *reinterpret_cast<const uint32_t*>(t + o);
+          else
+            e[LB * rr + j] = *reinterpret_cast<const uint16_t*>(t + o);
+        }
       }
     };
     lookup(0, ev[0]);
@@ -198,9 +218,18 @@ __global__ __launch_bounds__(64 * GNW, 4) void lut_gemv_kernel(
       float a0 = acc[2 * kp], a1 = acc[2 * kp + 1];
 #pragma unroll
       for (int j = 0; j < LB; ++j) {
-        const half2v xx = __builtin_bit_cast(half2v, xr[(LB * h + j) >> 1]);
-        a0 = fmaf((float)ev[bt & 1][j], (float)xx[j & 1], a0);
-        a1 = fmaf((float)ev[bt & 1][LB + j], (float)xx[j & 1], a1);
+        const int l = LB * h + j;                   // look-up within the group
+        if constexpr (PAIR) {
+          const half2v xx = __builtin_bit_cast(half2v, xr[l]);
+          a0 = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, ev[bt & 1][j]), xx, a0, false);
+          a1 = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, ev[bt & 1][LB + j]), xx, a1, false);
+        } else {
+          const half2v xx = __builtin_bit_cast(half2v, xr[l >> 1]);
+          const half2v e0 = __builtin_bit_cast(half2v, ev[bt & 1][j]);
+          const half2v e1 = __builtin_bit_cast(half2v, ev[bt & 1][LB + j]);
+          a0 = fmaf((float)e0[0], (float)xx[l & 1], a0);
+          a1 = fmaf((float)e1[0], (float)xx[l & 1], a1);
+        }
       }
       acc[2 * kp] = a0;
       acc[2 * kp + 1] = a1;
