@@ -388,18 +388,36 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
 
   // per-code sums over the row: lane l takes columns l, l + 64, ... (coalesced) and adds into
   // its own column of LDS bins; the 64 partial sums per code are then added in a fixed order
-  __shared__ float binD[16][64], binB[16][64];
-  __shared__ int binC[16][64];
+  __shared__ float binD[16][65], binB[16][65];      // 65: the 16 codes' partials fall into 16 banks
+  __shared__ int binC[16][65];
   for (int a = 0; a < C; ++a) {
     binD[a][tid] = 0.f;
     binB[a][tid] = 0.f;
     binC[a][tid] = 0;
   }
-  for (int64_t j = tid; j < n; j += 64) {
-    const int a = Q[i * ldq + j] & (C - 1);
-    binD[a][tid] += Hdiag[j];      // lane-private bins: plain read-modify-write
-    binB[a][tid] += G[i * ldg + j];
-    binC[a][tid] += 1;
+  // 16 columns per lane are fetched before the first is binned: the row of G comes from HBM,
+  // and one column at a time would pay that latency n / 64 times over
+  for (int64_t j0 = 0; j0 < n; j0 += 64 * 16) {
+    int qa[16];
+    float hv[16], gv[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int64_t j = j0 + tid + 64 * u;
+      const int64_t jc = (j < n) ? j : n - 1;       // clamped: the loads stay unconditional
+      const int qv = Q[i * ldq + jc];
+      qa[u] = (j < n) ? (qv & (C - 1)) : -1;
+      hv[u] = Hdiag[jc];
+      gv[u] = G[i * ldg + jc];
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int a = qa[u];
+      if (a >= 0) {
+        binD[a][tid] += hv[u];     // lane-private bins: plain read-modify-write
+        binB[a][tid] += gv[u];
+        binC[a][tid] += 1;
+      }
+    }
   }
   __syncthreads();
   if (tid < C) {
@@ -417,23 +435,44 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
   }
   __syncthreads();
   const double inv_s = (double)scale[1];
-  // M = sum of the per-group partial folds: coalesced reads, four running sums keep the loads
-  // of several groups in flight; then A = (M + M^T) / s + Diag(D)
+  // M = sum of the per-group partial folds (coalesced reads); then A = (M + M^T) / s + Diag(D)
   __shared__ double Ms[16][17];
   {
     const int64_t gs = mpad * C * C;
-    for (int e = tid; e < C * C; e += 64) {
-      const float* __restrict__ P = Apart + i * C * C + e;
-      double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-      int g = 0;
-      for (; g + 4 <= ngroups; g += 4) {
-        s0 += (double)P[(int64_t)g * gs];
-        s1 += (double)P[(int64_t)(g + 1) * gs];
-        s2 += (double)P[(int64_t)(g + 2) * gs];
-        s3 += (double)P[(int64_t)(g + 3) * gs];
+    // all loads of up to 16 groups x 4 entries are issued before the first is used: one round
+    // trip to memory instead of one per four groups
+    const float* __restrict__ P0 = Apart + i * C * C + tid;
+    double sacc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int g0 = 0; g0 < ngroups; g0 += 16) {
+      float v[4][16];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int g = 0; g < 16; ++g)
+        {
+          // clamped address, value discarded when out of range: the loads stay unconditional
+          const bool ok = tid + 64 * u < C * C && g0 + g < ngroups;
+          const float t = P0[(ok ? 64 * u : -tid) + (int64_t)(ok ? g0 + g : 0) * gs];
+          v[u][g] = ok ? t : 0.f;
+        }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        // fixed order: four interleaved running sums over the groups, as ((s0 + s1) + (s2 + s3))
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll
+        for (int g = 0; g < 16; g += 4) {
+          s0 += (double)v[u][g];
+          s1 += (double)v[u][g + 1];
+          s2 += (double)v[u][g + 2];
+          s3 += (double)v[u][g + 3];
+        }
+        sacc[u] += (s0 + s1) + (s2 + s3);
       }
-      for (; g < ngroups; ++g) s0 += (double)P[(int64_t)g * gs];
-      Ms[e / C][e % C] = (s0 + s1) + (s2 + s3);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = tid + 64 * u;
+      if (e < C * C) Ms[e / C][e % C] = sacc[u];
     }
   }
   __syncthreads();
@@ -444,54 +483,86 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
     A[a][b] = v;
   }
   __syncthreads();
-  // in-place Cholesky of the non-empty principal submatrix (lower), column by column
-  for (int k = 0; k < C; ++k) {
-    if (tid == 0) {
-      double d = A[k][k];
-      if (!dead[k]) {
-        // relative pivot tolerance: a code whose column is numerically dependent is dropped
-        if (!(d > 1e-10 * diag0[k]) || !(d < 1.79e308)) dead[k] = 2;
+  // Cholesky of the non-empty principal submatrix and the two triangular solves, in registers:
+  // lane r < C holds row r of the lower triangle; a value of another lane comes by v_readlane
+  // (the lane index is a compile-time constant in the unrolled loops), so the column-to-column
+  // chain has no LDS round trip and no barrier.  A code whose column is empty (count 0) or
+  // numerically dependent (pivot <= 1e-10 of its original diagonal, or not finite) is dropped:
+  // unit pivot, zero column, zero right-hand side.
+  auto bcast = [](double v, int src) {
+    const unsigned long long u = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)u, src);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(u >> 32), src);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+  };
+  const bool act = tid < C;
+  double a[16];
+#pragma unroll
+  for (int c = 0; c < 16; ++c) a[c] = (act && c <= tid) ? A[tid][c] : 0.0;
+  int dd = act ? dead[tid] : 1;
+  const double d0 = act ? diag0[tid] : 1.0;
+  double s = (act && !dd) ? rhs[tid] : 0.0;
+  double mydiag = 1.0;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    if (k < C) {
+      const double piv = bcast(a[k], k);
+      int dk = __builtin_amdgcn_readlane(dd, k);
+      const double d0k = bcast(d0, k);
+      if (!dk && (!(piv > 1e-10 * d0k) || !(piv < 1.79e308))) dk = 2;
+      const double dkk = dk ? 1.0 : sqrt(piv);
+      if (tid == k) {
+        dd = dk;
+        mydiag = dkk;
       }
-      A[k][k] = dead[k] ? 1.0 : sqrt(d);
-    }
-    __syncthreads();
-    const bool kd = dead[k] != 0;
-    const double dk = A[k][k];
-    if (tid > k && tid < C) A[tid][k] = (kd || dead[tid]) ? 0.0 : A[tid][k] / dk;
-    __syncthreads();
-    if (!kd) {
-      for (int e = tid; e < C * C; e += 64) {
-        const int r = e / C, c = e % C;
-        if (c > k && c <= r) A[r][c] -= A[r][k] * A[c][k];
+      const double l = (tid > k && !dk && !dd) ? a[k] / dkk : 0.0;     // L[r][k]
+      a[k] = (tid == k) ? dkk : l;
+      if (!dk) {
+#pragma unroll
+        for (int c = k + 1; c < 16; ++c)
+          if (c < C) a[c] -= l * bcast(l, c);       // used for c <= r only
       }
     }
-    __syncthreads();
   }
-  __shared__ double rdiagA[16];
-  if (tid < C) rdiagA[tid] = dead[tid] ? 0.0 : 1.0 / A[tid][tid];
+  // a pivot dropped after this lane's right-hand side was taken
+  if (dd) s = 0.0;
+  const double rd = (act && !dd) ? 1.0 / mydiag : 0.0;
+  // forward: y_k = s_k / L_kk, then s_r -= L[r][k] y_k for r > k
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    if (k < C) {
+      const double yk = bcast(s * rd, k);
+      if (tid == k) s = yk;
+      if (tid > k) s -= a[k] * yk;
+    }
+  }
+  // backward with L^T: lane r needs L[k][r], k > r, i.e. column r: through LDS once
   __syncthreads();
-  if (tid == 0) {
-    double y[16];
-    int nempty = 0;
-    for (int a = 0; a < C; ++a) {
-      double s = dead[a] ? 0.0 : rhs[a];
-      for (int q = 0; q < a; ++q) s -= A[a][q] * y[q];
-      y[a] = s * rdiagA[a];
+#pragma unroll
+  for (int c = 0; c < 16; ++c)
+    if (act && c <= tid) A[tid][c] = a[c];
+  __syncthreads();
+  double col[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) col[k] = (act && k > tid && k < C) ? A[k][tid] : 0.0;
+#pragma unroll
+  for (int k = 15; k >= 0; --k) {
+    if (k < C) {
+      const double xk = bcast(s * rd, k);
+      if (tid == k) s = xk;
+      if (tid < k) s -= col[k] * xk;
     }
-    for (int a = C - 1; a >= 0; --a) {
-      double s = y[a];
-      for (int q = a + 1; q < C; ++q) s -= A[q][a] * y[q];
-      y[a] = s * rdiagA[a];
+  }
+  if (act) {
+    if (dd) {
+      if (empty_mode == GANQ_EMPTY_ZERO || dd == 2) T[i * C + tid] = 0.f;
+    } else {
+      T[i * C + tid] = (float)s;
     }
-    for (int a = 0; a < C; ++a) {
-      if (dead[a]) {
-        ++nempty;
-        if (empty_mode == GANQ_EMPTY_ZERO || dead[a] == 2) T[i * C + a] = 0.f;
-      } else {
-        T[i * C + a] = (float)y[a];
-      }
-    }
-    if (empty_count != nullptr) empty_count[i] = nempty;
+  }
+  if (empty_count != nullptr) {
+    const unsigned long long dm = __builtin_amdgcn_ballot_w64(act && dd != 0);
+    if (tid == 0) empty_count[i] = __builtin_popcountll(dm);
   }
 }
 
