@@ -51,9 +51,17 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ X
   float mx = 0.f;
   for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
     const float* __restrict__ xr = X + r * ld;
-    for (int64_t k = threadIdx.x; k < cols; k += 256) {
-      const float v = fabsf(xr[k]);
-      if (v < __builtin_huge_valf() && v > mx) mx = v;
+    // eight loads in flight per thread; the index is clamped so that they stay unconditional
+    for (int64_t k0 = 0; k0 < cols; k0 += 8 * 256) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int64_t k = k0 + threadIdx.x + 256 * u;
+        v[u] = fabsf(xr[k < cols ? k : cols - 1]);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (v[u] < __builtin_huge_valf() && v[u] > mx) mx = v[u];
     }
   }
   red[threadIdx.x] = mx;
