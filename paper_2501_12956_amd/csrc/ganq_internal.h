@@ -37,6 +37,44 @@ constexpr int64_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + (kAlign - 1)) & ~(size_t)(kAlign - 1); }
 __host__ __device__ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Ascending bitonic sort of npow2 (a power of two) floats in LDS by a workgroup of 1024
+// threads; the caller has filled srt and synchronised.  Wavefront w owns the elements
+// [256 w', 256 w' + 256) for w' = w, w + 16, ...: a step whose partner distance j is below 256
+// stays inside such a segment, so it needs no workgroup barrier - the LDS operations of one
+// wavefront execute in order, and the wave barrier only keeps the compiler from moving them.
+// Only the steps with j >= 256 (10 of the 78 for 4096 elements) synchronise the workgroup.
+// Returns after a workgroup barrier.
+__device__ inline void bitonic_sort_lds_1024(float* srt, int npow2, int tid) {
+  const int wv = tid >> 6, ln = tid & 63;
+  for (int k = 2; k <= npow2; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      // compare-exchange t pairs elements e (bit log2(j) clear) and e | j: every lane is busy, and
+      // the 128 exchanges 128 S .. 128 S + 127 stay inside segment S when j < 256
+      for (int sg = wv; sg * 256 < npow2; sg += 16) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int t = 128 * sg + 64 * u + ln;
+          const int e = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+          const int partner = e | j;
+          if (partner < npow2) {
+            const bool up = (e & k) == 0;
+            const float a = srt[e], b = srt[partner];
+            if ((a > b) == up) {
+              srt[e] = b;
+              srt[partner] = a;
+            }
+          }
+        }
+      }
+      if (j >= 256 || (j >> 1) >= 256 || (j == 1 && k >= 256))
+        __syncthreads();          // this step or the next one crosses segments
+      else
+        __builtin_amdgcn_wave_barrier();
+    }
+  }
+  __syncthreads();
+}
+
 // Bump allocator over the caller's workspace.
 struct Arena {
   char* base;

@@ -17,39 +17,7 @@ __global__ __launch_bounds__(1024) void init_codebooks_kernel(const TW* __restri
   for (int e = tid; e < npow2; e += 1024)
     srt[e] = (e < n) ? (float)W[row * ldw + e] : __builtin_huge_valf();
   __syncthreads();
-  // Bitonic network.  Wavefront w owns the elements [256 w', 256 w' + 256) for w' = w, w + 16,
-  // ...: a step whose partner distance j is below 256 stays inside such a segment, so it needs
-  // no workgroup barrier - the LDS operations of one wavefront execute in order, and the
-  // wave barrier only keeps the compiler from moving them.  Only the steps with j >= 256 (10 of
-  // the 78 for 4096 elements) synchronise the workgroup.
-  const int wv = tid >> 6, ln = tid & 63;
-  for (int k = 2; k <= npow2; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      // compare-exchange t pairs elements e (bit log2(j) clear) and e | j: every lane is busy, and
-      // the 128 exchanges 128 S .. 128 S + 127 stay inside segment S when j < 256
-      for (int sg = wv; sg * 256 < npow2; sg += 16) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const int t = 128 * sg + 64 * u + ln;
-          const int e = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-          const int partner = e | j;
-          if (partner < npow2) {
-            const bool up = (e & k) == 0;
-            const float a = srt[e], b = srt[partner];
-            if ((a > b) == up) {
-              srt[e] = b;
-              srt[partner] = a;
-            }
-          }
-        }
-      }
-      if (j >= 256 || (j >> 1) >= 256 || (j == 1 && k >= 256))
-        __syncthreads();          // this step or the next one crosses segments
-      else
-        __builtin_amdgcn_wave_barrier();
-    }
-  }
-  __syncthreads();
+  bitonic_sort_lds_1024(srt, npow2, tid);
   if (tid < C) {
     const int s = tid;
     double val;

@@ -27,22 +27,7 @@ __global__ __launch_bounds__(1024) void outlier_cut_kernel(const TW* __restrict_
   for (int e = tid; e < npow2; e += 1024)
     srt[e] = (e < n) ? (float)W[row * ldw + e] : __builtin_huge_valf();
   __syncthreads();
-  for (int k = 2; k <= npow2; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int e = tid; e < npow2; e += 1024) {
-        const int partner = e ^ j;
-        if (partner > e) {
-          const bool up = (e & k) == 0;
-          const float a = srt[e], b = srt[partner];
-          if ((a > b) == up) {
-            srt[e] = b;
-            srt[partner] = a;
-          }
-        }
-      }
-      __syncthreads();
-    }
-  }
+  bitonic_sort_lds_1024(srt, npow2, tid);
   const float c_lo = srt[lower], c_up = srt[upper];
   int cnt = 0;
   for (int e = tid; e < n; e += 1024) {
