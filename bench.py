@@ -42,15 +42,15 @@ PEAK_F32_ADD_TOPS = 78.6
 # reading of a plain 1 GiB copy: x2.000 and x1.000); copied from profiles/bench_c3_hbm_traffic.txt,
 # which gives the commands.  Other configs report null.
 TRAFFIC_C3_BYTES = {
-    "hessian": (18506.65 + 580.14) * 2 ** 20,     # product kernel + reduction
-    "update_s": 1995.06 * 2 ** 20,
-    "t_accum": 820.03 * 2 ** 20,
-    "t_solve": 144.63 * 2 ** 20,
+    "hessian": (13128.79 + 580.15) * 2 ** 20,     # product kernel + reduction
+    "update_s": 1995.05 * 2 ** 20,
+    "t_accum": 820.07 * 2 ** 20,
+    "t_solve": 145.10 * 2 ** 20,
     "t_pad": 64.02 * 2 ** 20,
-    "gemm_wh": (946.24 + 2 * 64.05 + 2 * 128.01) * 2 ** 20,     # piece product + 2 x (absmax, split)
-    "loss": (946.24 + 2 * 64.05 + 2 * 128.01 + 146.03 + 128.15) * 2 ** 20,
-    "init": (96.02 + 64.28) * 2 ** 20,
-    "cholesky": (128.34 + 15 * 34.83 + 64 * 2.27) * 2 ** 20,
+    "gemm_wh": (951.10 + 2 * 64.10 + 2 * 128.01) * 2 ** 20,     # piece product + 2 x (absmax, split)
+    "loss": (951.10 + 2 * 64.10 + 2 * 128.01 + 146.03 + 128.15) * 2 ** 20,
+    "init": (96.02 + 64.33) * 2 ** 20,
+    "cholesky": (128.34 + 15 * 34.82 + 64 * 2.27) * 2 ** 20,
     "t_prep": (65.24 + 0.52) * 2 ** 20,
 }
 
