@@ -100,6 +100,21 @@ def test_argument_checks_run_on_the_host(lib):
                                    fake, fake, 8, None) == inv                       # reserved != 0
     assert lib.ganq_quantize_layer(h, fake, 1, 4, 8, 8, fake, 8, None, 0, 4, -1, None,
                                    fake, fake, 8, None) == inv
+    # deployment calls: stored-form geometry, alignment, CSR arrays all or none
+    assert lib.ganq_packed_row_bytes(4096, 4) == 2048 and lib.ganq_packed_row_bytes(4096, 3) == 1536
+    assert lib.ganq_packed_row_bytes(33, 3) == 32 and lib.ganq_packed_row_bytes(1, 1) == 16
+    assert lib.ganq_packed_row_bytes(0, 4) == 0 and lib.ganq_packed_row_bytes(8, 5) == 0
+    al = ctypes.c_void_p(0x1000)
+    assert lib.ganq_pack_layer(h, fake, 4, 64, 64, fake, 5, al, 32, fake) == inv        # nbits
+    assert lib.ganq_pack_layer(h, fake, 4, 64, 32, fake, 4, al, 32, fake) == inv        # ldq < n
+    assert lib.ganq_pack_layer(h, fake, 4, 64, 64, fake, 4, al, 16, fake) == inv        # ldp too small
+    assert lib.ganq_pack_layer(h, fake, 4, 64, 64, fake, 4, ctypes.c_void_p(0x1004), 32, fake) == inv
+    assert lib.ganq_pack_layer(h, fake, 70000, 64, 64, fake, 4, al, 32, fake) == b.GANQ_ERR_UNSUPPORTED
+    assert lib.ganq_lut_gemv(h, al, 24, fake, 4, 4, 64, fake, fake, None, None, None) == inv     # ldp % 16
+    assert lib.ganq_lut_gemv(h, al, 32, fake, 0, 4, 64, fake, fake, None, None, None) == inv     # nbits
+    assert lib.ganq_lut_gemv(h, al, 32, fake, 4, 4, 64, None, fake, None, None, None) == inv     # x
+    assert lib.ganq_lut_gemv(h, al, 32, fake, 4, 4, 64, fake, fake, fake, None, None) == inv     # partial CSR
+    assert lib.ganq_lut_gemv(None, al, 32, fake, 4, 4, 64, fake, fake, None, None, None) == inv
     assert b"" != lib.ganq_last_error(h)
     # empty problems are accepted without touching the GPU
     assert lib.ganq_update_S(h, None, 0, 8, 8, fake, 8, None, 4, None, 8, None, 0) == b.GANQ_OK
