@@ -397,13 +397,8 @@ hipError_t launch_cholesky(hipStream_t s, const float* H, int64_t n, int64_t ldh
   float* delta = reinterpret_cast<float*>(reinterpret_cast<char*>(info_dev) + kAlign);
   float* W = reinterpret_cast<float*>(reinterpret_cast<char*>(delta) + align_up((size_t)n * sizeof(float)));
   hipError_t e;
-  static bool attr_set = false;
-  if (!attr_set) {
-    e = hipFuncSetAttribute((const void*)chol_panel_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kPanelLds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_set{0};
+  if ((e = ensure_dynamic_lds((const void*)chol_panel_kernel, kPanelLds, lds_set)) != hipSuccess) return e;
   hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(1), 0, s, info_dev, 0);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (precond == GANQ_PRECOND_DIAGDOM) {

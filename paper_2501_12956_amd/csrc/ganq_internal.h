@@ -8,6 +8,8 @@
 #include <string>
 #include <vector>
 
+#include <atomic>
+
 #include "ganq.h"
 
 struct ganq_ctx {
@@ -73,6 +75,19 @@ __device__ inline void bitonic_sort_lds_1024(float* srt, int npow2, int tid) {
     }
   }
   __syncthreads();
+}
+
+// Raises a kernel's dynamic LDS limit once per device (the attribute is per device; `done`
+// holds one bit per device ordinal and belongs to that kernel's launcher).
+inline hipError_t ensure_dynamic_lds(const void* fn, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
 }
 
 // Bump allocator over the caller's workspace.

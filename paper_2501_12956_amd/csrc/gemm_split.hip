@@ -220,13 +220,8 @@ hipError_t launch_gemm_split(hipStream_t s, int64_t M, int64_t N, int64_t K, con
   _Float16* As = (_Float16*)((char*)scratch + kAlign);
   _Float16* Bs = (_Float16*)((char*)As + align_up((size_t)2 * M * k64 * sizeof(_Float16)));
   hipError_t e;
-  static bool attr_set = false;
-  if (!attr_set) {
-    e = hipFuncSetAttribute((const void*)gemm_split_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            2 * GSTAGEB);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_set{0};
+  if ((e = ensure_dynamic_lds((const void*)gemm_split_kernel, 2 * GSTAGEB, lds_set)) != hipSuccess) return e;
   // amax words are cleared by a small kernel (capturable, unlike a memset node)
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, amax, b_ready ? 1 : 2, 0u);
   if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -293,12 +293,10 @@ hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64
   const int ntiles = (int)(nt * (nt + 1) / 2);
   const int ngroups = (int)ceil_div(ntiles, 32), gsz = (int)ceil_div(ntiles, ngroups);
   dim3 grid((unsigned)(8 * ceil_div((int64_t)ngroups * split, 8) * 32));
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t ea = hipFuncSetAttribute((const void*)hessian_f16_kernel,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, HS * HSTAGEB);
+  static std::atomic<uint64_t> lds_set{0};
+  {
+    const hipError_t ea = ensure_dynamic_lds((const void*)hessian_f16_kernel, HS * HSTAGEB, lds_set);
     if (ea != hipSuccess) return ea;
-    attr_set = true;
   }
   hipLaunchKernelGGL(hessian_f16_kernel, grid, dim3(64 * HNW), HS * HSTAGEB, s, X, n, p, ldx, chunk,
                      (int)nt, ntiles, ngroups, gsz, split, partials);

@@ -641,12 +641,10 @@ static hipError_t launch_t_accum_n(hipStream_t s, int64_t m, int64_t n, void* sc
   const int mtiles = (int)(npad / TM);
   const int groups = t_groups(n);
   const int shmem = T_LDS_BYTES;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)t_accum_kernel<NBITS>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, shmem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
+  static std::atomic<uint64_t> lds_set{0};
+  {
+    const hipError_t ea = ensure_dynamic_lds((const void*)t_accum_kernel<NBITS>, shmem, lds_set);
+    if (ea != hipSuccess) return ea;
   }
   const int64_t total = (mpad / (TN >> NBITS)) * groups;
   hipLaunchKernelGGL(t_accum_kernel<NBITS>, dim3((unsigned)(8 * ceil_div(total, 8))), dim3(64 * TNW),
