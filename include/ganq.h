@@ -21,7 +21,9 @@
  *     device memory.
  *   - Errors are returned as ganq_status; nothing aborts or throws across the
  *     ABI.  Argument checks run on the host before any GPU work.
- *   - m and n up to 65535 (larger shapes return GANQ_ERR_UNSUPPORTED).
+ *   - m and n up to 65535; the S-update (and so ganq_quantize_layer) further
+ *     needs n * ldl * 4 bytes of L below 4 GiB, i.e. n <= 32767 for a packed L.
+ *     Larger shapes return GANQ_ERR_UNSUPPORTED.
  *   - nbits in [1, 4]; C = 2^nbits codes per row.  3 and 4 are the paper's
  *     settings (Section 4.1), 1 and 2 exist for brute-force tests.
  */
