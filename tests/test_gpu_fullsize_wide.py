@@ -1,6 +1,7 @@
-"""GPU parity at full size for the other layer shapes of the workload list: the LLaMA-7B
-down_proj-shaped layer (4096 x 11008, heavy-tailed activations with outlier channels) and the
-Llama-3-70B down_proj-shaped layer (8192 x 28672, 3.3 GB H and L).
+"""GPU parity at full size for the other layer shapes of the workload list: the 3-bit
+4096 x 4096 layer, the LLaMA-7B up_proj- and down_proj-shaped layers (11008 x 4096; 4096 x 11008
+with heavy-tailed activations and outlier channels) and the Llama-3-70B down_proj-shaped layer
+(8192 x 28672, 3.3 GB H and L).
 
 Nothing here can be checked whole by the float64 oracle in seconds, so every call is checked
 on what the oracle computes one by one, or on a property that holds at any size:
@@ -118,6 +119,14 @@ def run_layer(name, rows_s, rows_t):
         print("%s loss after S-update %.6e, after T-update %.6e" % (name, loss0, loss))
     finally:
         ctx.close()
+
+
+def test_q_proj_3bit_full_size():
+    run_layer("c2", rows_s=32, rows_t=16)
+
+
+def test_up_proj_7b_full_size():
+    run_layer("c4a", rows_s=32, rows_t=16)
 
 
 def test_down_proj_7b_full_size():
