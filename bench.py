@@ -4,9 +4,9 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3]
 
 One "step" is one pass of the whole hot path over one synthetic layer whose
-inputs already sit in HBM: H = X X^T, Cholesky, quantile codebooks, K_iters
-alternations of S-update and T-update (Algorithm 1), and one evaluation of the
-objective.  The headline workload is the LLaMA-7B q_proj-shaped layer at 4 bits
+inputs already sit in HBM: H = X X^T, then one call that factors H (Cholesky),
+builds the quantile codebooks and runs K_iters alternations of S-update and
+T-update (Algorithm 1), and one evaluation of the objective.  The headline workload is the LLaMA-7B q_proj-shaped layer at 4 bits
 (4096 x 4096, X 4096 x 262144 fp16, 10 alternations).
 
     python bench.py --decode [--config c5] [--nbits 4] [--steps K] [--warmup W]
@@ -246,14 +246,14 @@ def main():
     ctx = binding.Context(0)
     ctx.reserve(m, n, p, cfg.nbits)
     H = torch.empty(n, n, dtype=torch.float32, device=dev)
-    L = torch.empty(n, n, dtype=torch.float32, device=dev)
     Q = torch.empty(m, n, dtype=torch.uint8, device=dev)
     state = {}
 
     def step():
         ctx.build_hessian(X, H=H)
-        ctx.cholesky(H, L=L)
-        T, _ = ctx.quantize_layer(W, H, cfg.nbits, cfg.iters, L=L, Q=Q)     # T^0 built inside
+        # Cholesky, T^0 and the alternations in one call: the library factors H itself and runs what
+        # does not need L (W to fp32, T^0, G = W H, the split of H) beside the factorisation
+        T, _ = ctx.quantize_layer(W, H, cfg.nbits, cfg.iters, Q=Q)
         state["loss"] = ctx.layer_loss(Wf, H, T, Q, cfg.nbits)
         state["T"] = T
 

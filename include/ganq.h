@@ -13,7 +13,9 @@
  *     parameter name ends in _host.  The library never frees or keeps a
  *     caller pointer past the call.
  *   - Matrices are row-major with an explicit leading dimension in elements.
- *   - Work is enqueued on the context's HIP stream.  Calls that return a host
+ *   - Work is enqueued on the context's HIP stream (ganq_quantize_layer may
+ *     also use one internal stream, ordered after the context's stream at entry
+ *     and joined before it returns).  Calls that return a host
  *     scalar (info_host, loss_host, loss_history_host) synchronise that
  *     stream before returning; all others are asynchronous.
  *   - Scratch memory comes from a caller-provided workspace
@@ -170,7 +172,10 @@ ganq_status ganq_layer_loss(ganq_ctx* ctx, const float* W, int64_t m, int64_t n,
  * it).  loss_history_host (optional, 2*iters doubles) receives the objective
  * after every half step (index 2k: after the S-step of sweep k, 2k+1: after
  * its T-step); passing it adds one m x n x n product per half step.
- * opts == NULL means {NONE, 0, QUANTILE_MID, 0, ZERO}.  Synchronises. */
+ * opts == NULL means {NONE, 0, QUANTILE_MID, 0, ZERO}.  With L == NULL the work
+ * that does not depend on the factor (conversion of W, T^0, G = W H) runs on a
+ * second stream of the context beside the factorisation and is joined before
+ * the first sweep.  Synchronises. */
 ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype, int64_t m,
                                 int64_t n, int64_t ldw, const float* H, int64_t ldh,
                                 const float* L, int64_t ldl, int nbits, int iters,

@@ -39,6 +39,7 @@ ganq_status hip_fail(ganq_ctx* ctx, hipError_t e, const char* where) {
 struct ProfScope {
   ganq_ctx* ctx;
   int cls;
+  hipStream_t st;
   hipEvent_t a = nullptr, b = nullptr;
   bool live = false;
   static hipEvent_t get(ganq_ctx* c) {
@@ -51,16 +52,17 @@ struct ProfScope {
     if (hipEventCreate(&e) != hipSuccess) return nullptr;
     return e;
   }
-  ProfScope(ganq_ctx* c, int k) : ctx(c), cls(k) {
+  // events go on the stream the bracketed kernels are launched on
+  ProfScope(ganq_ctx* c, int k, hipStream_t on = nullptr) : ctx(c), cls(k), st(on != nullptr ? on : c->stream) {
     if (!c->prof_on) return;
     a = get(c);
     b = get(c);
     if (a == nullptr || b == nullptr) return;
-    live = hipEventRecord(a, c->stream) == hipSuccess;
+    live = hipEventRecord(a, st) == hipSuccess;
   }
   ~ProfScope() {
     if (!live) return;
-    if (hipEventRecord(b, ctx->stream) == hipSuccess)
+    if (hipEventRecord(b, st) == hipSuccess)
       ctx->prof_pending.push_back({cls, a, b});
     ctx->prof_launches[cls] += 1;
   }
@@ -174,6 +176,9 @@ ganq_status ganq_destroy(ganq_ctx* ctx) {
     hipEventDestroy(r.b);
   }
   for (auto e : ctx->prof_free) hipEventDestroy(e);
+  if (ctx->fork_ev != nullptr) hipEventDestroy(ctx->fork_ev);
+  if (ctx->join_ev != nullptr) hipEventDestroy(ctx->join_ev);
+  if (ctx->side != nullptr) hipStreamDestroy(ctx->side);
   delete ctx;
   return GANQ_OK;
 }
@@ -600,31 +605,18 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   hipStream_t s = ctx->stream;
   Arena ar(ctx->ws, ctx->ws_bytes);
 
-  const float* Wf = nullptr;
-  int64_t ldwf = ldw;
+  // all scratch is carved before the first launch: with the factorisation done here, the work
+  // that does not need L (conversion of W, T^0, G = W H, the split of H) runs on a second stream
+  // beside it, so none of these buffers may share space with the factorisation's scratch
+  float* Wbuf = nullptr;
   if (w_dtype == GANQ_F16) {
-    float* buf = (float*)ar.take((size_t)m * n * sizeof(float));
-    if (buf == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small (W)");
-    ProfScope prof(ctx, GANQ_K_INIT);
-    GANQ_HIP(ctx, launch_convert_f16_f32(s, (const _Float16*)W, m, n, ldw, buf, n));
-    Wf = buf;
-    ldwf = n;
-  } else {
-    Wf = (const float*)W;
+    Wbuf = (float*)ar.take((size_t)m * n * sizeof(float));
+    if (Wbuf == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small (W)");
   }
+  float* Lbuf = nullptr;
   if (L == nullptr) {
-    float* Lbuf = (float*)ar.take((size_t)n * n * sizeof(float));
+    Lbuf = (float*)ar.take((size_t)n * n * sizeof(float));
     if (Lbuf == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small (L)");
-    int64_t info = 0;
-    Arena sub((char*)ctx->ws + align_up(ar.off), ctx->ws_bytes - align_up(ar.off));
-    st = run_cholesky(ctx, sub, H, n, ldh, o.precond, o.lambda, Lbuf, n, &info);
-    if (st != GANQ_OK) return st;
-    L = Lbuf;
-    ldl = n;
-  }
-  if (o.init_codebooks) {
-    ProfScope prof(ctx, GANQ_K_INIT);
-    GANQ_HIP(ctx, launch_init_codebooks(s, Wf, 0, m, n, ldwf, nbits, (int)o.init, T));
   }
   float* G = (float*)ar.take((size_t)m * n * sizeof(float));
   void* s_scratch = ar.take(update_s_scratch_bytes(m, n));
@@ -632,15 +624,60 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   void* gs = ar.take(gemm_split_scratch_bytes(m, n, n));
   if (G == nullptr || s_scratch == nullptr || t_scratch == nullptr || gs == nullptr)
     return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small (solver scratch)");
-  if (iters > 0) {
-    {
-      ProfScope prof(ctx, GANQ_K_GEMM_WH);
-      GANQ_HIP(ctx, launch_gemm_split(s, m, n, n, Wf, ldwf, H, ldh, G, n, gs, 0));
-    }
-    // the fp16 split of H is made once per layer
-    ProfScope prof(ctx, GANQ_K_T_PREP);
-    GANQ_HIP(ctx, launch_t_prepare(s, H, m, n, ldh, nbits, t_scratch));
+
+  hipStream_t pre = s;               // stream of the work that does not need L
+  const bool forked = L == nullptr;
+  if (forked) {
+    if (ctx->side == nullptr) GANQ_HIP(ctx, hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
+    if (ctx->fork_ev == nullptr) GANQ_HIP(ctx, hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming));
+    if (ctx->join_ev == nullptr) GANQ_HIP(ctx, hipEventCreateWithFlags(&ctx->join_ev, hipEventDisableTiming));
+    pre = ctx->side;
+    GANQ_HIP(ctx, hipEventRecord(ctx->fork_ev, s));          // inputs produced earlier on the main stream
+    GANQ_HIP(ctx, hipStreamWaitEvent(pre, ctx->fork_ev, 0));
   }
+  const float* Wf = (const float*)W;
+  int64_t ldwf = ldw;
+  hipError_t pe = hipSuccess;        // first error on the second stream; checked after the join
+  auto pre_work = [&]() -> hipError_t {
+    hipError_t e;
+    if (w_dtype == GANQ_F16) {
+      ProfScope prof(ctx, GANQ_K_INIT, pre);
+      if ((e = launch_convert_f16_f32(pre, (const _Float16*)W, m, n, ldw, Wbuf, n)) != hipSuccess) return e;
+    }
+    if (o.init_codebooks) {
+      ProfScope prof(ctx, GANQ_K_INIT, pre);
+      if ((e = launch_init_codebooks(pre, Wf, 0, m, n, ldwf, nbits, (int)o.init, T)) != hipSuccess) return e;
+    }
+    if (iters > 0) {
+      {
+        ProfScope prof(ctx, GANQ_K_GEMM_WH, pre);
+        if ((e = launch_gemm_split(pre, m, n, n, Wf, ldwf, H, ldh, G, n, gs, 0)) != hipSuccess) return e;
+      }
+      // the fp16 split of H is made once per layer
+      ProfScope prof(ctx, GANQ_K_T_PREP, pre);
+      if ((e = launch_t_prepare(pre, H, m, n, ldh, nbits, t_scratch)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+  };
+  if (w_dtype == GANQ_F16) {
+    Wf = Wbuf;
+    ldwf = n;
+  }
+  pe = pre_work();
+  if (forked) {
+    if (pe == hipSuccess) pe = hipEventRecord(ctx->join_ev, pre);
+    int64_t info = 0;
+    Arena sub((char*)ctx->ws + align_up(ar.off), ctx->ws_bytes - align_up(ar.off));
+    st = run_cholesky(ctx, sub, H, n, ldh, o.precond, o.lambda, Lbuf, n, &info);
+    if (st != GANQ_OK || pe != hipSuccess) {
+      hipStreamSynchronize(pre);     // nothing of this call may still run when it returns
+      if (st != GANQ_OK) return st;
+    }
+    L = Lbuf;
+    ldl = n;
+  }
+  GANQ_HIP(ctx, pe);
+  if (forked) GANQ_HIP(ctx, hipStreamWaitEvent(s, ctx->join_ev, 0));
 
   for (int k = 0; k < iters; ++k) {
     {

@@ -26,6 +26,10 @@ struct ganq_ctx {
   std::vector<hipEvent_t> prof_free;
   double prof_ms[GANQ_K_COUNT] = {0};
   int64_t prof_launches[GANQ_K_COUNT] = {0};
+  // second stream (default priority) and two events: work of one call that does not depend on
+  // the factorisation runs beside it; always joined before the call returns
+  hipStream_t side = nullptr;
+  hipEvent_t fork_ev = nullptr, join_ev = nullptr;
 };
 
 namespace ganq {
