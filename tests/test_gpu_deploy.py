@@ -137,3 +137,30 @@ def test_lut_gemv_full_size(ctx, name, nbits):
     worst = check_product(y[rt].cpu().numpy().astype(np.float64), lut[rt].cpu().numpy(), Q[rt].cpu().numpy(),
                           x.cpu().numpy())
     print("%s N=%d full size: max |dy| / sum|terms| = %.2e" % (name, nbits, worst))
+
+
+def test_lut_gemv_strided_storage_unaligned_x_and_empty_outlier_rows(ctx):
+    """Rows of the stored form further apart than their bytes, an activation vector that is only
+    2-byte aligned (the lanes then fetch it element by element) and CSR rows without entries."""
+    m, n, nbits = 21, 2100, 4
+    T, Q, x = random_layer(m, n, nbits, 77)
+    packed, lut = ctx.pack_layer(torch.from_numpy(Q).cuda(), torch.from_numpy(T).cuda(), nbits)
+    rb = packed.shape[1]
+    wide = torch.zeros(m, rb + 48, dtype=torch.uint8, device="cuda")
+    wide[:, :rb] = packed
+    xbuf = torch.zeros(n + 1, dtype=torch.float16, device="cuda")
+    xbuf[1:] = torch.from_numpy(x).cuda()
+    rng = np.random.default_rng(4)
+    Ws = np.zeros((m, n))
+    for i in (0, 5, 20):                                   # all other rows have no outliers
+        cols = rng.choice(n, size=70, replace=False)       # more than one wavefront pass
+        Ws[i, cols] = rng.standard_normal(70)
+    Ws = Ws.astype(np.float32)
+    nz = [np.flatnonzero(Ws[i]) for i in range(m)]
+    row_ptr = torch.tensor(np.concatenate([[0], np.cumsum([len(c) for c in nz])]), dtype=torch.int64).cuda()
+    col = torch.tensor(np.concatenate(nz), dtype=torch.int32).cuda()
+    val = torch.tensor(np.concatenate([Ws[i, c] for i, c in enumerate(nz)]), dtype=torch.float32).cuda()
+    y = ctx.lut_gemv(wide[:, :rb], lut, nbits, n, xbuf[1:], outliers=(row_ptr, col, val))
+    check_product(y.cpu().numpy().astype(np.float64), lut.cpu().numpy(), Q, x, Ws.astype(np.float64))
+    y0 = ctx.lut_gemv(packed, lut, nbits, n, torch.from_numpy(x).cuda(), outliers=(row_ptr, col, val))
+    assert torch.equal(y, y0)
