@@ -3,7 +3,7 @@ inputs, stage by stage (each call of the two implementations is fed identical
 inputs), plus the degenerate cases.  Sizes span several tiles and a ragged tail
 while staying small enough for the oracle to finish in seconds.
 
-Tolerances (derived from the arithmetic):
+Tolerances (derived from the arithmetic of the kernels):
   H        |dH_jk| <= h_tol(p) sqrt(H_jj H_kk), h_tol = max(2e-6, 5 eps sqrt(p/3)): fp32 running
            sums of p products (sequential accumulation error, 4.5 sigma over n^2 entries)
   L        |L L^T - H|_F <= 2e-6 |H|_F, |L - L_ref|_F <= 1e-4 |L_ref|_F
