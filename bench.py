@@ -87,6 +87,7 @@ def cpu_baseline(cfg, X_dev, W_dev, rows=256, tokens=16384):
     scaled to the whole layer (rows are independent; H is a sum over tokens)."""
     import numpy as np
     from oracle import ganq_ref as ref
+    tokens, rows = min(tokens, cfg.p), min(rows, cfg.m)
     try:
         from threadpoolctl import threadpool_info
         threads = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
