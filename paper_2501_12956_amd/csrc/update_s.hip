@@ -10,11 +10,14 @@
 // synchronisation.  Columns are taken in blocks of 64 from the right:
 //   phase 1  acc[16 x 64] = E[16 x later columns] * L[later rows, block]
 //            on the matrix cores (v_mfma_f32_16x16x4_f32).  The later columns
-//            are split over the 4 wavefronts; each wavefront streams its share
+//            are split over the 8 wavefronts; each wavefront streams its share
 //            of L straight from L2 into registers, software-pipelined 8 MFMA
-//            groups deep, and the 4 partial tiles are summed through LDS in a
+//            groups deep, and the 8 partial tiles are summed through LDS in a
 //            fixed order.  This is the sum of Eq. (22) restricted to columns
-//            right of the block, re-associated.
+//            right of the block, re-associated.  The share is walked from the
+//            oldest columns to the newest, so its first fragments do not depend
+//            on the block being decided and are requested before that block's
+//            phase 2 starts.
 //   phase 2  the 64 columns of the block one by one, 16 lanes per row.  Each
 //            row's codebook is sorted once (stable); lane c holds the midpoint
 //            between sorted codes c and c+1, so the nearest code of a target
@@ -165,6 +168,58 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
   const float mid = (c < 15) ? 0.5f * (ts + tnext) : __builtin_huge_valf();
   const int gshift = 16 * g;
 
+  // Far part of a block that starts at column jb, over the rows k >= ks.  This wavefront takes
+  // the k-quads qd = wv, wv + NW, ...: iteration r covers rows k = ks + 4 wv + 4 NW r + g
+  // (g = lane / 16), and the iterations run from the last one (oldest columns) down to 0, so
+  // that the newest residuals are needed last.  Operands come through buffer loads: a scalar
+  // resource descriptor based at row ks + 4 wv, a scalar byte offset per iteration and a fixed
+  // 32-bit lane offset, so a load costs no vector ALU work, and rows k >= n fall outside the
+  // descriptor's range and read as zero (which is what the ragged tail and the padding of the
+  // iteration count to whole chunks need).
+  struct Far {
+    __amdgpu_buffer_rsrc_t rl, re;
+    uint32_t nch;        // chunks of PU iterations
+    bool active;
+  };
+  const int wv = __builtin_amdgcn_readfirstlane(wave);
+  const uint32_t loff = (uint32_t)((g * ldl + 4 * c) * sizeof(float));
+  const uint32_t eoff = (uint32_t)((g * SR + c) * sizeof(float));
+  const uint32_t lstep = (uint32_t)(4 * NW * ldl * sizeof(float));   // bytes per iteration in L
+  const uint32_t estep = (uint32_t)(4 * NW * SR * sizeof(float));    // bytes per iteration in E
+  auto far_setup = [&](int64_t jb, int64_t ks) {
+    Far F;
+    const int64_t krow = ks + 4 * wv;
+    F.active = ks < n && krow < n;
+    F.nch = 0;
+    const int64_t kr = F.active ? krow : 0;
+    const int64_t lbytes = F.active ? ((n - 1 - kr) * ldl + n - jb) * (int64_t)sizeof(float) : 0;
+    const int64_t ebytes = F.active ? (n - kr) * SR * (int64_t)sizeof(float) : 0;
+    F.rl = __builtin_amdgcn_make_buffer_rsrc((void*)(L + kr * ldl + jb), 0, (int)lbytes, 0x00020000);
+    F.re = __builtin_amdgcn_make_buffer_rsrc((void*)(Eslab + kr * SR), 0, (int)ebytes, 0x00020000);
+    if (F.active) {
+      // iterations of this wavefront that touch at least one row < n, in chunks of PU
+      const uint32_t niter = (uint32_t)ceil_div(n - krow, 4 * NW);
+      F.nch = (niter + PU - 1) / PU;
+    }
+    return F;
+  };
+  auto far_fetch = [&](const Far& F, uint32_t it) {
+    const uint32_t r = F.nch * PU - 1 - it;
+    LFrag f;
+    f.a = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.re, eoff, r * estep, 0));
+    if (VECL) {
+      f.b = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(F.rl, loff, r * lstep, 0));
+    } else {
+      f.b.x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff, r * lstep, 0));
+      f.b.y = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff + 4, r * lstep, 0));
+      f.b.z = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff + 8, r * lstep, 0));
+      f.b.w = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff + 12, r * lstep, 0));
+    }
+    return f;
+  };
+  LFrag fa[PU], fb[PU];
+  bool prefetched = false;     // fa already holds the first chunk of the coming far part
+
   const int nblk = (int)ceil_div(n, SB);
   for (int b = nblk - 1; b >= 0; --b) {
     const int64_t j0 = (int64_t)b * SB;
@@ -203,60 +258,29 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
     floatx4 macc[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) macc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-    if (kstart < n) {
-      // This wavefront takes the k-quads qd = wv, wv + NW, ...: iteration `it` covers rows
-      // k = kstart + 4 wv + 4 NW it + g (g = lane / 16).  Operands come through buffer loads:
-      // a scalar resource descriptor based at row kstart + 4 wv, a scalar byte offset per
-      // iteration and a fixed 32-bit lane offset, so a load costs no vector ALU work, and
-      // rows k >= n fall outside the descriptor's range and read as zero (which is what
-      // the ragged tail needs).
-      const int wv = __builtin_amdgcn_readfirstlane(wave);
-      const int64_t krow = kstart + 4 * wv;
-      LFrag fa[PU], fb[PU];
-      if (krow < n) {
-        const int64_t lbytes = ((n - 1 - krow) * ldl + n - j0) * (int64_t)sizeof(float);
-        const int64_t ebytes = (n - krow) * SR * (int64_t)sizeof(float);
-        const __amdgpu_buffer_rsrc_t rl = __builtin_amdgcn_make_buffer_rsrc(
-            (void*)(L + krow * ldl + j0), 0, (int)lbytes, 0x00020000);
-        const __amdgpu_buffer_rsrc_t re = __builtin_amdgcn_make_buffer_rsrc(
-            (void*)(Eslab + krow * SR), 0, (int)ebytes, 0x00020000);
-        const uint32_t loff = (uint32_t)((g * ldl + 4 * c) * sizeof(float));
-        const uint32_t eoff = (uint32_t)((g * SR + c) * sizeof(float));
-        const uint32_t lstep = (uint32_t)(4 * NW * ldl * sizeof(float));   // bytes per iteration in L
-        const uint32_t estep = (uint32_t)(4 * NW * SR * sizeof(float));    // bytes per iteration in E
-        auto fetch = [&](uint32_t it) {
-          LFrag f;
-          f.a = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(re, eoff, it * estep, 0));
-          if (VECL) {
-            f.b = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rl, loff, it * lstep, 0));
-          } else {
-            f.b.x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, loff, it * lstep, 0));
-            f.b.y = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, loff + 4, it * lstep, 0));
-            f.b.z = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, loff + 8, it * lstep, 0));
-            f.b.w = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rl, loff + 12, it * lstep, 0));
-          }
-          return f;
-        };
+    {
+      const Far F = far_setup(j0, kstart);
+      if (F.active) {
         auto mma = [&](const LFrag& f) {
           macc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.x, macc[0], 0, 0, 0);
           macc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.y, macc[1], 0, 0, 0);
           macc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.z, macc[2], 0, 0, 0);
           macc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.w, macc[3], 0, 0, 0);
         };
-        // iterations of this wavefront that touch at least one row < n, in chunks of PU
-        const uint32_t niter = (uint32_t)ceil_div(n - krow, 4 * NW);
-        const uint32_t nch = (niter + PU - 1) / PU;
         // Two register sets of PU fragments: while the matrix cores consume one set, the
         // loads that refill the other are issued between the MFMA groups (one fragment per
-        // group of 4 MFMAs); the scheduling barriers pin that interleaving.
+        // group of 4 MFMAs); the scheduling barriers pin that interleaving.  The first set
+        // may already be on its way (fetched during the previous block).
+        if (!prefetched) {
 #pragma unroll
-        for (int u = 0; u < PU; ++u) fa[u] = fetch(u);
+          for (int u = 0; u < PU; ++u) fa[u] = far_fetch(F, u);
+        }
         bool in_a = true;
-        for (uint32_t ch = 0; ch + 1 < nch; ++ch) {
+        for (uint32_t ch = 0; ch + 1 < F.nch; ++ch) {
           if (in_a) {
 #pragma unroll
             for (int u = 0; u < PU; ++u) {
-              fb[u] = fetch((ch + 1) * PU + u);
+              fb[u] = far_fetch(F, (ch + 1) * PU + u);
               __builtin_amdgcn_sched_barrier(0);
               mma(fa[u]);
               __builtin_amdgcn_sched_barrier(0);
@@ -264,7 +288,7 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
           } else {
 #pragma unroll
             for (int u = 0; u < PU; ++u) {
-              fa[u] = fetch((ch + 1) * PU + u);
+              fa[u] = far_fetch(F, (ch + 1) * PU + u);
               __builtin_amdgcn_sched_barrier(0);
               mma(fb[u]);
               __builtin_amdgcn_sched_barrier(0);
@@ -292,7 +316,21 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
 #pragma unroll
       for (int i = 0; i < 4; ++i) Ld[rr][cc + i] = (cc + i < rr) ? stg[u][i] : 0.f;
     }
-    __syncthreads();
+    // The next block's far part starts with its oldest rows (largest k), which do not depend on
+    // this block's decisions: its first fragments are requested now and arrive while the
+    // sequential phase runs.
+    prefetched = false;
+    if (b > 0) {
+      const Far Fn = far_setup(j0 - SB, j0);
+      if (Fn.active && Fn.nch >= 2) {
+#pragma unroll
+        for (int u = 0; u < PU; ++u) fa[u] = far_fetch(Fn, u);
+        prefetched = true;
+      }
+    }
+    // only LDS traffic is handed over here: a full __syncthreads would also wait for the loads
+    // just issued
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
     if (p2) {
       // MFMA tile t, lane l', register v holds (row 4*(l'/16) + v, local column 4*(l'%16) + t)
