@@ -137,3 +137,12 @@ def test_product_path_has_no_oracle_import():
                 assert "oracle" not in text or f == "synth.py", f
     text = open(os.path.join(pkg, "synth.py")).read()
     assert "import oracle" not in text and "from oracle" not in text
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                         text=True, timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
