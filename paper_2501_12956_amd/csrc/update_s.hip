@@ -17,7 +17,10 @@
 //            right of the block, re-associated.  The share is walked from the
 //            oldest columns to the newest, so its first fragments do not depend
 //            on the block being decided and are requested before that block's
-//            phase 2 starts.
+//            phase 2 starts.  Phase 2 keeps only four of the eight wavefronts
+//            busy; the other four spend it on the oldest rows (up to 1792) of
+//            the next block's sum, which are final by then, and carry the
+//            result over in registers.
 //   phase 2  the 64 columns of the block one by one, 16 lanes per row.  Each
 //            row's codebook is sorted once (stable); lane c holds the midpoint
 //            between sorted codes c and c+1, so the nearest code of a target
@@ -38,6 +41,8 @@ constexpr int SB = 64;          // columns per block
 constexpr int SR = kSlabRows;   // rows per workgroup
 constexpr int PU = 8;           // MFMA groups per software-pipeline stage
 constexpr int NW = 8;           // wavefronts per workgroup (phase 1 splits k over all of them)
+constexpr int64_t EARLY_MAX = 1792;  // most rows of a far part that are multiplied one block early
+constexpr int64_t EARLY_MIN = 128;   // fewer than this are not worth a loop of their own
 
 template <int CTRL>
 __device__ inline float dpp_f(float v) {
@@ -179,46 +184,108 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
   struct Far {
     __amdgpu_buffer_rsrc_t rl, re;
     uint32_t nch;        // chunks of PU iterations
+    uint32_t lstep, estep;   // bytes per iteration in L and in E
     bool active;
   };
   const int wv = __builtin_amdgcn_readfirstlane(wave);
   const uint32_t loff = (uint32_t)((g * ldl + 4 * c) * sizeof(float));
   const uint32_t eoff = (uint32_t)((g * SR + c) * sizeof(float));
-  const uint32_t lstep = (uint32_t)(4 * NW * ldl * sizeof(float));   // bytes per iteration in L
-  const uint32_t estep = (uint32_t)(4 * NW * SR * sizeof(float));    // bytes per iteration in E
-  auto far_setup = [&](int64_t jb, int64_t ks) {
+  // rows [ks, ke) of the far part, shared by nwq wavefronts of which this one is number wq
+  auto far_setup = [&](int64_t jb, int64_t ks, int64_t ke, int wq, int nwq) {
     Far F;
-    const int64_t krow = ks + 4 * wv;
-    F.active = ks < n && krow < n;
+    const int64_t krow = ks + 4 * wq;
+    F.active = wq >= 0 && krow < ke;
     F.nch = 0;
+    F.lstep = (uint32_t)(4 * nwq * ldl * sizeof(float));
+    F.estep = (uint32_t)(4 * nwq * SR * sizeof(float));
     const int64_t kr = F.active ? krow : 0;
-    const int64_t lbytes = F.active ? ((n - 1 - kr) * ldl + n - jb) * (int64_t)sizeof(float) : 0;
-    const int64_t ebytes = F.active ? (n - kr) * SR * (int64_t)sizeof(float) : 0;
+    const int64_t lbytes = F.active ? ((ke - 1 - kr) * ldl + n - jb) * (int64_t)sizeof(float) : 0;
+    const int64_t ebytes = F.active ? (ke - kr) * SR * (int64_t)sizeof(float) : 0;
     F.rl = __builtin_amdgcn_make_buffer_rsrc((void*)(L + kr * ldl + jb), 0, (int)lbytes, 0x00020000);
     F.re = __builtin_amdgcn_make_buffer_rsrc((void*)(Eslab + kr * SR), 0, (int)ebytes, 0x00020000);
     if (F.active) {
-      // iterations of this wavefront that touch at least one row < n, in chunks of PU
-      const uint32_t niter = (uint32_t)ceil_div(n - krow, 4 * NW);
+      // iterations of this wavefront that touch at least one row < ke, in chunks of PU
+      const uint32_t niter = (uint32_t)ceil_div(ke - krow, 4 * nwq);
       F.nch = (niter + PU - 1) / PU;
     }
     return F;
   };
+  // The oldest rows of a block's far part are final one block early, so the wavefronts that
+  // have no rows in the sequential phase multiply them while that phase runs for the block
+  // before: rows [n - early_rows(K), n) of a far part of K rows.
+  auto early_rows = [&](int64_t K) -> int64_t {
+    // what stays for all wavefronts is a whole number of double chunks (2 PU iterations each),
+    // so that loop has no padding and its first chunk can be requested ahead
+    constexpr int64_t CH = 4 * NW * PU * 2;
+    if (K < CH + EARLY_MIN) return 0;
+    int64_t a = ceil_div(K - EARLY_MAX, CH);
+    if (a < 1) a = 1;
+    return K - a * CH;
+  };
   auto far_fetch = [&](const Far& F, uint32_t it) {
     const uint32_t r = F.nch * PU - 1 - it;
     LFrag f;
-    f.a = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.re, eoff, r * estep, 0));
+    f.a = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.re, eoff, r * F.estep, 0));
     if (VECL) {
-      f.b = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(F.rl, loff, r * lstep, 0));
+      f.b = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(F.rl, loff, r * F.lstep, 0));
     } else {
-      f.b.x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff, r * lstep, 0));
-      f.b.y = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff + 4, r * lstep, 0));
-      f.b.z = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff + 8, r * lstep, 0));
-      f.b.w = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff + 12, r * lstep, 0));
+      f.b.x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff, r * F.lstep, 0));
+      f.b.y = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff + 4, r * F.lstep, 0));
+      f.b.z = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff + 8, r * F.lstep, 0));
+      f.b.w = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff + 12, r * F.lstep, 0));
     }
     return f;
   };
   LFrag fa[PU], fb[PU];
   bool prefetched = false;     // fa already holds the first chunk of the coming far part
+  // Two register sets of PU fragments: while the matrix cores consume one set, the loads that
+  // refill the other are issued between the MFMA groups (one fragment per group of 4 MFMAs);
+  // the scheduling barriers pin that interleaving.  The first set may already be on its way.
+  auto far_run = [&](const Far& F, floatx4 (&macc)[4], bool have_first) {
+    if (!F.active) return;
+    auto mma = [&](const LFrag& f) {
+      macc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.x, macc[0], 0, 0, 0);
+      macc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.y, macc[1], 0, 0, 0);
+      macc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.z, macc[2], 0, 0, 0);
+      macc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.w, macc[3], 0, 0, 0);
+    };
+    if (!have_first) {
+#pragma unroll
+      for (int u = 0; u < PU; ++u) fa[u] = far_fetch(F, u);
+    }
+    bool in_a = true;
+    for (uint32_t ch = 0; ch + 1 < F.nch; ++ch) {
+      if (in_a) {
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+          fb[u] = far_fetch(F, (ch + 1) * PU + u);
+          __builtin_amdgcn_sched_barrier(0);
+          mma(fa[u]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+          fa[u] = far_fetch(F, (ch + 1) * PU + u);
+          __builtin_amdgcn_sched_barrier(0);
+          mma(fb[u]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      in_a = !in_a;
+    }
+    if (in_a) {
+#pragma unroll
+      for (int u = 0; u < PU; ++u) mma(fa[u]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < PU; ++u) mma(fb[u]);
+    }
+  };
+  floatx4 mearly[4];           // sums over the rows of the coming far part that were done early
+#pragma unroll
+  for (int t = 0; t < 4; ++t) mearly[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+  int64_t kearly = n;          // first of those rows
 
   const int nblk = (int)ceil_div(n, SB);
   for (int b = nblk - 1; b >= 0; --b) {
@@ -255,55 +322,14 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
     }
 
     // ---- phase 1: acc = E[:, kstart:] * L[kstart:, block] on the matrix cores ----
+    // The rows [kearly, n) were multiplied during the previous block's sequential phase (their
+    // sums wait in mearly of the wavefronts that did it); all wavefronts share the rest.
     floatx4 macc[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) macc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < 4; ++t) macc[t] = mearly[t];
     {
-      const Far F = far_setup(j0, kstart);
-      if (F.active) {
-        auto mma = [&](const LFrag& f) {
-          macc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.x, macc[0], 0, 0, 0);
-          macc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.y, macc[1], 0, 0, 0);
-          macc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.z, macc[2], 0, 0, 0);
-          macc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a, f.b.w, macc[3], 0, 0, 0);
-        };
-        // Two register sets of PU fragments: while the matrix cores consume one set, the
-        // loads that refill the other are issued between the MFMA groups (one fragment per
-        // group of 4 MFMAs); the scheduling barriers pin that interleaving.  The first set
-        // may already be on its way (fetched during the previous block).
-        if (!prefetched) {
-#pragma unroll
-          for (int u = 0; u < PU; ++u) fa[u] = far_fetch(F, u);
-        }
-        bool in_a = true;
-        for (uint32_t ch = 0; ch + 1 < F.nch; ++ch) {
-          if (in_a) {
-#pragma unroll
-            for (int u = 0; u < PU; ++u) {
-              fb[u] = far_fetch(F, (ch + 1) * PU + u);
-              __builtin_amdgcn_sched_barrier(0);
-              mma(fa[u]);
-              __builtin_amdgcn_sched_barrier(0);
-            }
-          } else {
-#pragma unroll
-            for (int u = 0; u < PU; ++u) {
-              fa[u] = far_fetch(F, (ch + 1) * PU + u);
-              __builtin_amdgcn_sched_barrier(0);
-              mma(fb[u]);
-              __builtin_amdgcn_sched_barrier(0);
-            }
-          }
-          in_a = !in_a;
-        }
-        if (in_a) {
-#pragma unroll
-          for (int u = 0; u < PU; ++u) mma(fa[u]);
-        } else {
-#pragma unroll
-          for (int u = 0; u < PU; ++u) mma(fb[u]);
-        }
-      }
+      const Far F = far_setup(j0, kstart, kearly, wv, NW);
+      far_run(F, macc, prefetched);
     }
 #pragma unroll
     for (int t = 0; t < 4; ++t)
@@ -316,16 +342,21 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
 #pragma unroll
       for (int i = 0; i < 4; ++i) Ld[rr][cc + i] = (cc + i < rr) ? stg[u][i] : 0.f;
     }
-    // The next block's far part starts with its oldest rows (largest k), which do not depend on
-    // this block's decisions: its first fragments are requested now and arrive while the
-    // sequential phase runs.
+    // The next block's far part: its oldest rows (largest k) do not depend on this block's
+    // decisions.  The wavefronts without rows in the sequential phase multiply a stretch of them
+    // during that phase; the others request the first fragments of what remains, which arrive
+    // while the sequential phase runs.
     prefetched = false;
+    int64_t kearly_next = n;
     if (b > 0) {
-      const Far Fn = far_setup(j0 - SB, j0);
-      if (Fn.active && Fn.nch >= 2) {
+      kearly_next = n - early_rows(n - j0);
+      if (p2) {
+        const Far Fn = far_setup(j0 - SB, j0, kearly_next, wv, NW);
+        if (Fn.active && Fn.nch >= 2) {
 #pragma unroll
-        for (int u = 0; u < PU; ++u) fa[u] = far_fetch(Fn, u);
-        prefetched = true;
+          for (int u = 0; u < PU; ++u) fa[u] = far_fetch(Fn, u);
+          prefetched = true;
+        }
       }
     }
     // only LDS traffic is handed over here: a full __syncthreads would also wait for the loads
@@ -369,6 +400,15 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
         }
       }
     }
+    else {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) mearly[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+      if (b > 0) {
+        const Far Fe = far_setup(j0 - SB, kearly_next, n, wv - 4, NW - 4);
+        far_run(Fe, mearly, false);
+      }
+    }
+    kearly = kearly_next;
     __syncthreads();   // E of this block visible to all wavefronts; LDS reusable
   }
 }

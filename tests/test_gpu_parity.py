@@ -185,7 +185,11 @@ def test_init_codebooks(ctx, m, n, nbits, dtype):
 
 # ----------------------------------------------------------------------------- S-update
 @pytest.mark.parametrize("m,n,nbits", [(40, 200, 4), (16, 64, 3), (33, 65, 4), (1, 1, 2), (7, 130, 1),
-                                       (50, 257, 2)])
+                                       (50, 257, 2),
+                                       # long enough that part of a block's sum over later columns is
+                                       # taken one block early, with and without its row limit, even
+                                       # and odd row strides of L
+                                       (20, 1501, 4), (16, 1536, 4), (17, 2901, 3), (5, 2880, 2)])
 def test_update_S_stagewise(ctx, m, n, nbits):
     W, X = make_problem(m, n, max(4 * n, 64), nbits)
     H64 = ref.build_hessian(X.numpy())
