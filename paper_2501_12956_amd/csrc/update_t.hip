@@ -9,17 +9,27 @@
 //
 // is a GEMM whose left operand is the strictly lower triangle of H and whose
 // right operand is the one-hot expansion of Q, kept in LDS and updated in place
-// from precomputed positions.  One-hot entries are exact in fp16; H is split into two fp16
-// pieces (hi + lo, 22 significant bits, pre-scaled by a power of two so that the
-// largest entry sits near 2^15), both accumulated in fp32 by
-// v_mfma_f32_32x32x16_f16.  Only k < j is visited (H is symmetric):
+// from precomputed positions.  It runs in integer arithmetic on
+// v_mfma_i32_32x32x32_i8 (twice the fp16 rate, exact accumulation):
+//   H_jk ~ v_jk 2^(e_k - s_j),  v_jk an integer of 16 or 24 bits,
+// with a power-of-two column factor 2^e_k (e_k = 0..6, from the diagonal, so that a row's
+// entries use the same digits whether their column is large or small; it is the value of
+// the one-hot entry, which an int8 operand can hold) and a power-of-two row factor chosen
+// so that the row's largest |v| fills the digits and sum_k |v_jk| 2^e_k < 2^30 (no subset
+// sum can overflow an int32).  v is split into balanced base-256 digits, one GEMM pass per
+// digit from the top, the accumulators shifted left by 8 between passes, so the accumulator
+// ends as sum_k v_jk 2^e_k [Q_ik == b] exactly.  A tile of 128 rows takes two digits when
+// every row's scaled off-diagonal entries stay below 1/16 of the diagonal scale
+// sqrt(H_jj max_k H_kk) - the absolute error of an entry is then at most that of 20-bit
+// digits on a fully correlated row - and three digits otherwise.
+// Only k < j is visited (H is symmetric):
 //   M_i[a, b] = sum_j [Q_ij == a] Z[j, (i,b)],   A_i = M_i + M_i^T + Diag(D_i),
 //   D_i[a] = sum_{j: Q_ij == a} H_jj.
 // The fold over j runs on the matrix cores as well, straight from the accumulator
-// registers (see t_accum_kernel); partial M_i per group of row tiles of H go to
-// scratch and are summed in float64 by the solve kernel, which also forms D_i and
-// b_i, drops unused codes (pseudo-inverse reading: their entry is 0, or kept) and
-// solves the reduced system by Cholesky in float64.
+// registers and with the row factor 2^-s_j as the left operand (see t_accum_kernel); partial
+// M_i per group of row tiles of H go to scratch and are summed in float64 by the solve
+// kernel, which also forms D_i and b_i, drops unused codes (pseudo-inverse reading: their
+// entry is 0, or kept) and solves the reduced system by Cholesky in float64.
 #include "ganq_internal.h"
 
 namespace ganq {
@@ -27,20 +37,27 @@ namespace {
 
 constexpr int TM = 128;    // rows j of H per tile
 constexpr int TN = 512;    // (row i, code b) pairs per workgroup
-constexpr int TK = 32;     // k per stage
+constexpr int TK = 64;     // k per stage
 constexpr int TNW = 8;     // wavefronts per workgroup, each 128 x 64 of the tile
+constexpr int TP = 3;      // most base-256 digits per entry
+constexpr int EMAX = 6;    // largest column exponent (the one-hot entry 2^e is an int8)
+constexpr float V2MAX = 32512.f;     // largest |v| with two digits:  127 * 256 + 127 - 127
+constexpr float V3MAX = 8323072.f;   // with three: 2^23 - 2^16
 
-// ---- per-layer preparation: fp16 hi/lo split of the strictly lower triangle of H ----
-__global__ __launch_bounds__(256) void maxdiag_kernel(const float* __restrict__ H, int64_t n,
-                                                      int64_t ldh, float* __restrict__ scale,
-                                                      float* __restrict__ Hdiag) {
+// ---- per-layer preparation ----
+// diagonal of H, column exponents e_k = clamp(EMAX + round(log2 sqrt(H_kk / max H)), 0, EMAX)
+// (stored as the one-hot value 2^e_k), two digits per tile until a row says otherwise
+__global__ __launch_bounds__(256) void t_diag_kernel(const float* __restrict__ H, int64_t n,
+                                                     int64_t ldh, int64_t npad, int mtiles,
+                                                     float* __restrict__ scale,
+                                                     float* __restrict__ Hdiag,
+                                                     uint8_t* __restrict__ Cs, int* __restrict__ Ptile) {
   __shared__ float red[256];
   float mx = 0.f;
   for (int64_t j = threadIdx.x; j < n; j += 256) {
     const float d = H[j * ldh + j];
     Hdiag[j] = d;
-    const float ad = fabsf(d);
-    if (ad < __builtin_huge_valf() && ad > mx) mx = ad;
+    if (d < __builtin_huge_valf() && d > mx) mx = d;
   }
   red[threadIdx.x] = mx;
   __syncthreads();
@@ -48,39 +65,119 @@ __global__ __launch_bounds__(256) void maxdiag_kernel(const float* __restrict__ 
     if ((int)threadIdx.x < w) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + w]);
     __syncthreads();
   }
+  const float hmax = red[0];
+  for (int64_t k = threadIdx.x; k < npad; k += 256) {
+    int e = 0;
+    if (k < n && hmax > 0.f) {
+      const float d = Hdiag[k];
+      if (d > 0.f && d < __builtin_huge_valf()) {
+        const float t = (float)EMAX + rintf(0.5f * log2f(d / hmax));
+        e = t < 0.f ? 0 : (t > (float)EMAX ? EMAX : (int)t);
+      }
+    }
+    Cs[k] = (uint8_t)(1 << e);
+  }
+  for (int t = threadIdx.x; t < mtiles; t += 256) Ptile[t] = 2;
   if (threadIdx.x == 0) {
-    float s = 1.f;
-    if (red[0] > 0.f) s = ldexpf(1.f, 14 - ilogbf(red[0]));   // max * s in [2^14, 2^15)
-    scale[0] = s;
-    scale[1] = 1.f / s;
+    scale[0] = 1.f;
+    scale[1] = 1.f;     // the fold applies the row factors; nothing is left for the solve
+    scale[2] = hmax;
   }
 }
 
-// Hs[j][k / 32][piece][k % 32]: the hi and lo pieces of 32 consecutive k share one 128-byte
-// line, which is what one row of an LDS stage holds.
-__global__ __launch_bounds__(256) void split_lower_kernel(const float* __restrict__ H, int64_t n,
-                                                          int64_t ldh, int64_t npad,
-                                                          const float* __restrict__ scale,
-                                                          _Float16* __restrict__ Hs) {
+// Row j: largest |H_jk| 2^-e_k and sum |H_jk| over k < j give the row exponents for two and
+// for three digits; the row asks for three digits when its scaled entries are not small
+// against the diagonal scale.
+__global__ __launch_bounds__(256) void t_rowscale_kernel(const float* __restrict__ H, int64_t n,
+                                                         int64_t ldh, const float* __restrict__ scale,
+                                                         const float* __restrict__ Hdiag,
+                                                         const uint8_t* __restrict__ Cs,
+                                                         int8_t* __restrict__ S2,
+                                                         int8_t* __restrict__ S3,
+                                                         int* __restrict__ Ptile) {
+  __shared__ float rmx[256], rsum[256];
+  const int64_t j = blockIdx.x;
+  float mx = 0.f, sum = 0.f;
+  if (j < n) {
+    for (int64_t k = threadIdx.x; k < j; k += 256) {
+      const float a = fabsf(H[j * ldh + k]);
+      sum += a;
+      mx = fmaxf(mx, a / (float)Cs[k]);
+    }
+  }
+  rmx[threadIdx.x] = mx;
+  rsum[threadIdx.x] = sum;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      rmx[threadIdx.x] = fmaxf(rmx[threadIdx.x], rmx[threadIdx.x + w]);
+      rsum[threadIdx.x] += rsum[threadIdx.x + w];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x != 0) return;
+  mx = rmx[0];
+  sum = rsum[0];
+  int s2 = 0, s3 = 0;
+  if (mx > 0.f && mx < __builtin_huge_valf() && sum < __builtin_huge_valf()) {
+    const int t = 29 - ilogbf(sum);                 // sum 2^t in [2^29, 2^30)
+    s2 = 14 - ilogbf(mx);
+    if (ldexpf(mx, s2) > V2MAX) --s2;
+    s3 = 22 - ilogbf(mx);
+    if (ldexpf(mx, s3) > V3MAX) --s3;
+    s2 = s2 < t ? s2 : t;
+    s3 = s3 < t ? s3 : t;
+    s2 = s2 < -120 ? -120 : (s2 > 120 ? 120 : s2);
+    s3 = s3 < -120 ? -120 : (s3 > 120 ? 120 : s3);
+    const float dj = Hdiag[j];
+    const bool small = dj > 0.f && dj < __builtin_huge_valf() &&
+                       mx * (float)(1 << EMAX) * 16.f <= sqrtf(dj) * sqrtf(scale[2]);
+    if (!small) atomicMax(&Ptile[j / TM], 3);
+  }
+  S2[j] = (int8_t)s2;
+  S3[j] = (int8_t)s3;
+}
+
+// Hs[digit][j][k], digit 0 the most significant one; only the tiles the GEMM reads
+__global__ __launch_bounds__(256) void t_split_kernel(const float* __restrict__ H, int64_t n,
+                                                      int64_t ldh, int64_t npad,
+                                                      const uint8_t* __restrict__ Cs,
+                                                      const int8_t* __restrict__ S2,
+                                                      const int8_t* __restrict__ S3,
+                                                      const int* __restrict__ Ptile,
+                                                      int8_t* __restrict__ Hs,
+                                                      float* __restrict__ Wj) {
   const int64_t j = blockIdx.y;                                   // row of H
   const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;      // column
   if (k >= npad) return;
-  // only tiles that the GEMM reads: k-tile <= j-tile (tiles of TM)
   if (k / TM > j / TM) return;
-  _Float16 hi = (_Float16)0, lo = (_Float16)0;
+  const int P = Ptile[j / TM];
+  const int sj = (j < n) ? ((P == 2) ? S2[j] : S3[j]) : 0;
+  if (k == 0) Wj[j] = ldexpf(1.f, -sj);
+  int iv = 0;
   if (j < n && k < j) {
-    const float v = H[j * ldh + k] * scale[0];
-    hi = (_Float16)v;
-    lo = (_Float16)(v - (float)hi);
+    const float lim = (P == 2) ? V2MAX : V3MAX;
+    float v = rintf(ldexpf(H[j * ldh + k], sj) / (float)Cs[k]);
+    v = (v == v) ? fminf(fmaxf(v, -lim), lim) : 0.f;
+    iv = (int)v;
   }
-  const int64_t o = j * 2 * npad + (k >> 5) * 64 + (k & 31);
-  Hs[o] = hi;
-  Hs[o + 32] = lo;
+  const int d0 = (int)(int8_t)(iv & 0xff);
+  const int v1 = (iv - d0) >> 8;
+  const int64_t o = j * npad + k, ps = npad * npad;
+  if (P == 2) {
+    Hs[o] = (int8_t)v1;
+    Hs[ps + o] = (int8_t)d0;
+  } else {
+    const int d1 = (int)(int8_t)(v1 & 0xff);
+    Hs[o] = (int8_t)((v1 - d1) >> 8);
+    Hs[ps + o] = (int8_t)d1;
+    Hs[2 * ps + o] = (int8_t)d0;
+  }
 }
 
 // Zero-padded copy of Q (Qp, one byte per index, read by the fold) and, for the one-hot
-// staging of the GEMM, the byte offset of each index's 1 inside the one-hot LDS tile (Qo):
-// row (i mod RW) * C + code of TK halfs, 16-byte chunks XOR-permuted by (row >> 1) & 3.
+// staging of the GEMM, the byte offset of each index's entry inside the one-hot LDS tile (Qo):
+// row (i mod RW) * C + code of TK bytes, 16-byte chunks XOR-permuted by (row >> 1) & 3.
 __global__ __launch_bounds__(256) void pad_q_kernel(const uint8_t* __restrict__ Q, int64_t m,
                                                     int64_t n, int64_t ldq, int64_t npad, int nbits,
                                                     uint8_t* __restrict__ Qp,
@@ -92,26 +189,26 @@ __global__ __launch_bounds__(256) void pad_q_kernel(const uint8_t* __restrict__ 
   const int code = (i < m && k < n) ? (Q[i * ldq + k] & (C - 1)) : 0;
   Qp[i * npad + k] = (uint8_t)code;
   const int nrow = (int)(i % RW) * C + code, kk = (int)(k & (TK - 1));
-  Qo[i * npad + k] = (uint16_t)(nrow * (TK * 2) + ((((kk >> 3) ^ (nrow >> 1)) & 3) << 4) + (kk & 7) * 2);
+  Qo[i * npad + k] = (uint16_t)(nrow * TK + ((((kk >> 4) ^ (nrow >> 1)) & 3) << 4) + (kk & 15));
 }
 
 // ---- the GEMM with fold epilogue ----
-// LDS: T_S stages of { A tile: TM rows x 128 bytes (hi | lo of 32 k), one-hot B tile: TN rows
+// LDS: T_S stages of { A tile: TM rows x 64 bytes (one digit of 64 k), one-hot B tile: TN rows
 // x 64 bytes }.  A tiles arrive by direct-to-LDS buffer loads; such a load writes 64 x 16
 // consecutive bytes, so rows cannot be padded and the 16-byte chunks of a row are stored in
-// XOR-permuted order instead (A: chunk c of row r at c ^ (r & 7); B: c ^ ((r >> 1) & 3)).
+// XOR-permuted order instead (chunk c of row r at c ^ ((r >> 1) & 3), both tiles).
 // The one-hot tile is never rebuilt: it starts as zeros and each thread owns a fixed set of
-// (row i, k) positions whose single 1 it moves - it clears the 1 it wrote when the stage
+// (row i, k) positions whose single entry it moves - it clears the one it wrote when the stage
 // was last used and sets the new one (in-order LDS writes of one thread).
 constexpr int T_S = 3;
-constexpr int T_AROWB = 128;
-constexpr int T_ATILEB = TM * T_AROWB;
-constexpr int T_BROWB = TK * 2;
-constexpr int T_BTILEB = TN * T_BROWB;
+constexpr int T_ROWB = TK;
+constexpr int T_ATILEB = TM * T_ROWB;
+constexpr int T_BTILEB = TN * T_ROWB;
 constexpr int T_STAGEB = T_ATILEB + T_BTILEB;
 constexpr int T_LDS_BYTES = T_S * T_STAGEB;
 
 typedef int int4v __attribute__((ext_vector_type(4)));
+typedef int intx16 __attribute__((ext_vector_type(16)));
 
 // One wavefront-wide direct load: lane l's 16 bytes land at LDS byte lds_addr + 16 l.  The
 // compiler does not see these loads; the kernel waits for them (vmcnt) before the barrier
@@ -125,29 +222,33 @@ __device__ inline void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: 
 template <int V> struct IntC { static constexpr int value = V; };
 
 // Workgroup = (slab of RW rows i, group g of row tiles {g, mtiles - 1 - g} of H): every
-// workgroup runs the same number of k-steps.  Three LDS stages and one barrier per k-step:
-// the barrier at the top of step k publishes the data of step k + 1 and frees the stage of
-// step k - 1, which is refilled for step k + 2; the first MFMA fragments of step k + 1 are
-// read during step k, so no wavefront starts a step waiting for LDS.
+// workgroup runs the same number of k-steps per digit.  Three LDS stages and one barrier per
+// k-step: the barrier at the top of step k publishes the data of step k + 1 and frees the
+// stage of step k - 1, which is refilled for step k + 2; the first MFMA fragments of step
+// k + 1 are read during step k, so no wavefront starts a step waiting for LDS.
 //
-// The fold  M_i[a, b] += [Q_ij == a] Z[j, (i, b)]  is an outer product per row j, and
+// The fold  M_i[a, b] += [Q_ij == a] 2^-s_j Z[j, (i, b)]  is an outer product per row j, and
 // v_mfma_f32_16x16x1_4b_f32 computes four independent 16 x 16 outer products per
 // instruction, one per group of 16 lanes.  In the 32 x 32 accumulator tile lane l holds
 // column l % 32 and register v holds one row j per lane half, so the 16-lane groups are
-// (lane half, 16-column half) and register v itself is the right operand; the left operand
-// is [code of (this lane's row i, that j) == l % C].  With C < 16 a 16-column group spans
-// several rows i and only the diagonal C x C blocks of the 16 x 16 result are meaningful;
-// the others are never stored.
+// (lane half, 16-column half) and register v itself (converted to float) is the right
+// operand; the left operand is 2^-s_j where the code of (this lane's row i, that j) equals
+// l % C, else 0.  With C < 16 a 16-column group spans several rows i and only the diagonal
+// C x C blocks of the 16 x 16 result are meaningful; the others are never stored.
 template <int NBITS>
-__global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __restrict__ Hs,
+__global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const int8_t* __restrict__ Hs,
                                                            int64_t npad, const uint8_t* __restrict__ Qp,
                                                            const uint16_t* __restrict__ Qo,
+                                                           const uint8_t* __restrict__ Cs,
+                                                           const float* __restrict__ Wj,
+                                                           const int* __restrict__ Ptile,
                                                            int64_t mpad, int mtiles, int ngroups,
                                                            float* __restrict__ Apart) {
   constexpr int C = 1 << NBITS;
   constexpr int RW = TN >> NBITS;             // rows i per workgroup
   constexpr int EPT = (RW * TK) / (64 * TNW); // one-hot positions per thread and stage
   constexpr int EW = EPT / 2;                 // dwords of offsets per thread and stage
+  constexpr int CW = EPT / 4;                 // dwords of one-hot values per thread and stage
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
 
@@ -173,35 +274,33 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __res
   // one-hot staging: this thread owns row il and the EPT consecutive k from kk0 of every
   // stage.  q3..q0 hold the packed tile offsets of the last three scattered steps and of the
   // next one; the stage written for step s held step s - 3 (stages rotate over all steps of
-  // the workgroup, across both row tiles), so its ones are cleared with q3.  Before the first
-  // steps the "old" positions are this thread's own code-0 positions (zeros already).
+  // the workgroup, across digits and row tiles), so its entries are cleared with q3.  Before
+  // the first steps the "old" positions are this thread's own code-0 positions (zeros already).
   const int ex_il = (tid * EPT) / TK, ex_kk0 = (tid * EPT) % TK;
   const uint32_t* __restrict__ qorow = reinterpret_cast<const uint32_t*>(Qo + (i0 + ex_il) * npad + ex_kk0);
-  uint32_t q3[EW], q2[EW], q1[EW], q0[EW];
+  const uint32_t* __restrict__ csrow = reinterpret_cast<const uint32_t*>(Cs + ex_kk0);
+  uint32_t q3[EW], q2[EW], q1[EW], q0[EW], cv[CW];
 #pragma unroll
   for (int w = 0; w < EW; ++w) {
     uint32_t pk = 0;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int nrow = ex_il * C, kk = ex_kk0 + 2 * w + h;
-      pk |= (uint32_t)(nrow * T_BROWB + ((((kk >> 3) ^ (nrow >> 1)) & 3) << 4) + (kk & 7) * 2) << (16 * h);
+      pk |= (uint32_t)(nrow * T_ROWB + ((((kk >> 4) ^ (nrow >> 1)) & 3) << 4) + (kk & 15)) << (16 * h);
     }
     q3[w] = q2[w] = q1[w] = pk;
     q0[w] = pk;
   }
 
-  // direct loads of the A tile: one instruction covers 8 rows x 128 bytes
-  const int dr = lane >> 3;
-  const int dc = (lane & 7) ^ dr;
-  uint32_t voff[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j)
-    voff[j] = (uint32_t)(((int64_t)((wave + TNW * j) * 8 + dr) * npad * 4) + dc * 16);
+  // direct load of the A tile: one instruction covers 16 rows x 64 bytes, one per wavefront
+  const int dr = lane >> 2;
+  const int dc = (lane & 3) ^ ((dr >> 1) & 3);
+  const uint32_t voff = (uint32_t)((int64_t)(wave * 16 + dr) * npad + dc * 16);
 
-  const int rswzA = l32 & 7, rswzB = (l32 >> 1) & 3;
+  const int rswz = (l32 >> 1) & 3;
   // per-lane LDS byte offsets of the fragments inside a stage
-  const int aoff = l32 * T_AROWB;
-  const int boff = T_ATILEB + (wave * 64 + l32) * T_BROWB;
+  const int aoff = l32 * T_ROWB;
+  const int boff = T_ATILEB + (wave * 64 + l32) * T_ROWB;
   int st = 0;                // stage of the next k-step; rotates over all steps of the workgroup
   __syncthreads();
 
@@ -209,115 +308,125 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __res
     const int mt = (half == 0) ? group : mtiles - 1 - group;
     if (half == 1 && mt == group) break;
     const int64_t jt0 = (int64_t)mt * TM;
-    const int nk = (int)((jt0 + TM) / TK);    // tiles right of the diagonal are never needed (nk >= 4)
+    const int nk = (int)((jt0 + TM) / TK);    // tiles right of the diagonal are never needed (nk >= 2)
+    const int P = __builtin_amdgcn_readfirstlane(Ptile[mt]);
 
-    int4v rsA;
-    {
-      const uint64_t ad = (uint64_t)(uintptr_t)(Hs + jt0 * 2 * npad);
-      rsA[0] = (int)(uint32_t)ad;
-      rsA[1] = (int)(uint32_t)((ad >> 32) & 0xffffu);
-      rsA[2] = (int)(uint32_t)((int64_t)TM * npad * 4);
-      rsA[3] = 0x00020000;
-    }
-    auto issue = [&](int k, int st) {
-      const uint32_t soff = (uint32_t)k * 128u;
-      const uint32_t sbase = lds0 + st * T_STAGEB;
-#pragma unroll
-      for (int j = 0; j < 2; ++j) load16_to_lds(rsA, sbase + (wave + TNW * j) * 1024, voff[j], soff);
-    };
     auto load_q = [&](int k) {
 #pragma unroll
       for (int w = 0; w < EW; ++w) q0[w] = qorow[(k * TK) / 2 + w];
+#pragma unroll
+      for (int w = 0; w < CW; ++w) cv[w] = csrow[(k * TK) / 4 + w];
     };
-    // clear the ones of the step that used this stage last (q3), set those of q0, rotate
+    // clear the entries of the step that used this stage last (q3), set those of q0, rotate
     auto scatter = [&](int st) {
       unsigned char* Bs = smem + st * T_STAGEB + T_ATILEB;
 #pragma unroll
       for (int w = 0; w < EW; ++w) {
-        *reinterpret_cast<_Float16*>(Bs + (q3[w] & 0xffffu)) = (_Float16)0;
-        *reinterpret_cast<_Float16*>(Bs + (q3[w] >> 16)) = (_Float16)0;
-        *reinterpret_cast<_Float16*>(Bs + (q0[w] & 0xffffu)) = (_Float16)1;
-        *reinterpret_cast<_Float16*>(Bs + (q0[w] >> 16)) = (_Float16)1;
+        Bs[q3[w] & 0xffffu] = 0;
+        Bs[q3[w] >> 16] = 0;
+      }
+#pragma unroll
+      for (int w = 0; w < EW; ++w) {
+        Bs[q0[w] & 0xffffu] = (unsigned char)((cv[w >> 1] >> (16 * (w & 1))) & 0xffu);
+        Bs[q0[w] >> 16] = (unsigned char)((cv[w >> 1] >> (16 * (w & 1) + 8)) & 0xffu);
         q3[w] = q2[w];
         q2[w] = q1[w];
         q1[w] = q0[w];
       }
     };
 
-    floatx16 acc[4][2];
+    intx16 acc[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+        for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0;
 
     struct Frags {
-      half8 ahi[4], alo[4], bf[2];
+      int4v a[4], b[2];
     };
     auto load_frags = [&](Frags& f, int st, int ks) {
       const unsigned char* S0 = smem + st * T_STAGEB;
-      const int c = 2 * ks + kh;
+      const int cs = ((2 * ks + kh) ^ rswz) << 4;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        f.ahi[i] = *reinterpret_cast<const half8*>(S0 + aoff + i * 32 * T_AROWB + ((c ^ rswzA) << 4));
-        f.alo[i] = *reinterpret_cast<const half8*>(S0 + aoff + i * 32 * T_AROWB + (((4 + c) ^ rswzA) << 4));
-      }
+      for (int i = 0; i < 4; ++i)
+        f.a[i] = *reinterpret_cast<const int4v*>(S0 + aoff + i * 32 * T_ROWB + cs);
 #pragma unroll
       for (int jn = 0; jn < 2; ++jn)
-        f.bf[jn] = *reinterpret_cast<const half8*>(S0 + boff + jn * 32 * T_BROWB + ((c ^ rswzB) << 4));
+        f.b[jn] = *reinterpret_cast<const int4v*>(S0 + boff + jn * 32 * T_ROWB + cs);
     };
     auto mma = [&](const Frags& f) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn)
-          acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.ahi[i], f.bf[jn], acc[i][jn], 0, 0, 0);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int jn = 0; jn < 2; ++jn)
-          acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.alo[i], f.bf[jn], acc[i][jn], 0, 0, 0);
+          acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.a[i], f.b[jn], acc[i][jn], 0, 0, 0);
     };
 
-    // every stage is free here (start of the kernel, or the barrier after the previous fold)
-    {
-      const int st1 = (st == 2) ? 0 : st + 1;
-      load_q(0);
-      issue(0, st);
-      issue(1, st1);
-      scatter(st);
-      load_q(1);
-      scatter(st1);
-      load_q(2);
-    }
-    wait_all_loads();
-    __syncthreads();
-    Frags f0, f1;
-    load_frags(f0, st, 0);   // step 0 repeats the barrier, which costs nothing here
+    for (int dg = 0; dg < P; ++dg) {
+      int4v rsA;
+      {
+        const uint64_t ad = (uint64_t)(uintptr_t)(Hs + ((int64_t)dg * npad + jt0) * npad);
+        rsA[0] = (int)(uint32_t)ad;
+        rsA[1] = (int)(uint32_t)((ad >> 32) & 0xffffu);
+        rsA[2] = (int)(uint32_t)((int64_t)TM * npad);
+        rsA[3] = 0x00020000;
+      }
+      auto issue = [&](int k, int st) {
+        load16_to_lds(rsA, lds0 + st * T_STAGEB + wave * 1024, voff, (uint32_t)k * (uint32_t)TK);
+      };
+      if (dg > 0) {
+        // next digit: everything so far moves up by one digit
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] <<= 8;
+      }
 
-    // One k-step.  PRODUCE: stage the operands of step k + 2 (the Q offsets of step k + 3
-    // are fetched with a clamped index so that the load is unconditional).  PREFETCH: read
-    // the first fragments of step k + 1.
-    auto step = [&](int k, auto PRODUCE, auto PREFETCH) {
-      const int st1 = (st == 2) ? 0 : st + 1, st2 = (st == 0) ? 2 : st - 1;
+      // every stage is free here (start of the kernel, or the barrier after the previous pass)
+      {
+        const int st1 = (st == 2) ? 0 : st + 1;
+        load_q(0);
+        issue(0, st);
+        issue(1, st1);
+        scatter(st);
+        load_q(1);
+        scatter(st1);
+        load_q(nk > 2 ? 2 : nk - 1);
+      }
       wait_all_loads();
       __syncthreads();
-      if constexpr (decltype(PRODUCE)::value != 0) {
-        scatter(st2);
-        load_q(k + 3 < nk ? k + 3 : nk - 1);
-        issue(k + 2, st2);
-      }
-      load_frags(f1, st, 1);
-      mma(f0);
-      if constexpr (decltype(PREFETCH)::value != 0) load_frags(f0, st1, 0);
-      mma(f1);
-      st = st1;
-    };
+      Frags f0, f1;
+      load_frags(f0, st, 0);   // step 0 repeats the barrier, which costs nothing here
+
+      // One k-step.  PRODUCE: stage the operands of step k + 2 (the Q offsets of step k + 3
+      // are fetched with a clamped index so that the load is unconditional).  PREFETCH: read
+      // the first fragments of step k + 1.
+      auto step = [&](int k, auto PRODUCE, auto PREFETCH) {
+        const int st1 = (st == 2) ? 0 : st + 1, st2 = (st == 0) ? 2 : st - 1;
+        wait_all_loads();
+        __syncthreads();
+        if constexpr (decltype(PRODUCE)::value != 0) {
+          scatter(st2);
+          load_q(k + 3 < nk ? k + 3 : nk - 1);
+          issue(k + 2, st2);
+        }
+        load_frags(f1, st, 1);
+        mma(f0);
+        if constexpr (decltype(PREFETCH)::value != 0) load_frags(f0, st1, 0);
+        mma(f1);
+        st = st1;
+      };
 #pragma unroll 1
-    for (int k = 0; k < nk - 2; ++k) step(k, IntC<1>{}, IntC<1>{});
-    step(nk - 2, IntC<0>{}, IntC<1>{});
-    step(nk - 1, IntC<0>{}, IntC<0>{});
+      for (int k = 0; k < nk - 2; ++k) step(k, IntC<1>{}, IntC<1>{});
+      step(nk - 2, IntC<0>{}, IntC<1>{});
+      step(nk - 1, IntC<0>{}, IntC<0>{});
+      // the LDS stages are reused by the next pass; slower wavefronts may still be reading
+      __syncthreads();
+    }
 
     // fold: register v of tile (i, jn) is row j = i*32 + (v>>2)*8 + kh*4 + (v&3) of the tile.
     // D[jn] = four 16 x 16 blocks (lane half, column half) of column tile jn.
@@ -330,6 +439,7 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __res
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       uint32_t qd[2][4];
+      float4 wj[4];
 #pragma unroll
       for (int jn = 0; jn < 2; ++jn) {
         const int il = (wave * 64 + jn * 32 + l32) >> NBITS;
@@ -338,13 +448,19 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __res
         for (int vq = 0; vq < 4; ++vq) qd[jn][vq] = *reinterpret_cast<const uint32_t*>(qr + vq * 8);
       }
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
+      for (int vq = 0; vq < 4; ++vq)
+        wj[vq] = *reinterpret_cast<const float4*>(Wj + jt0 + i * 32 + kh * 4 + vq * 8);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float4 w4 = wj[v >> 2];
+        const float wv = (v & 3) == 0 ? w4.x : (v & 3) == 1 ? w4.y : (v & 3) == 2 ? w4.z : w4.w;
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn) {
           const int code = (int)((qd[jn][v >> 2] >> (8 * (v & 3))) & 0xffu);
-          const float sel = (code == acmp) ? 1.f : 0.f;
-          D[jn] = __builtin_amdgcn_mfma_f32_16x16x1f32(sel, acc[i][jn][v], D[jn], 0, 0, 0);
+          const float sel = (code == acmp) ? wv : 0.f;
+          D[jn] = __builtin_amdgcn_mfma_f32_16x16x1f32(sel, (float)acc[i][jn][v], D[jn], 0, 0, 0);
         }
+      }
     }
     // D[jn][4 B + r] = block B = 2 * (lane half of the source) + (16-column half), element
     // (row 4 (lane / 16) + r, column lane % 16): rows are (i', a), columns (i'', b) within the
@@ -365,8 +481,6 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const _Float16* __res
           if (half == 1) v += *dst;
           *dst = v;
         }
-    // the LDS stages are reused by the next row tile; slower wavefronts may still be reading
-    __syncthreads();
   }
 }
 
@@ -573,7 +687,12 @@ inline int t_groups(int64_t n) { return (int)((ceil_div(n, TM) + 1) / 2); }
 struct TScratch {
   float* scale;
   float* Hdiag;
-  _Float16* Hs;
+  uint8_t* Cs;
+  float* Wj;
+  int8_t* S2;
+  int8_t* S3;
+  int* Ptile;
+  int8_t* Hs;
   uint8_t* Qp;
   uint16_t* Qo;
   float* Apart;
@@ -584,16 +703,26 @@ inline size_t t_layout(int64_t m, int64_t n, int nbits, char* base, TScratch* ou
   const int C = 1 << nbits;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-  const size_t o_scale = take(2 * sizeof(float));
+  const size_t o_scale = take(4 * sizeof(float));
   const size_t o_diag = take((size_t)n * sizeof(float));
-  const size_t o_hs = take((size_t)2 * npad * npad * sizeof(_Float16));
+  const size_t o_cs = take((size_t)npad);
+  const size_t o_wj = take((size_t)npad * sizeof(float));
+  const size_t o_s2 = take((size_t)npad);
+  const size_t o_s3 = take((size_t)npad);
+  const size_t o_pt = take((size_t)(npad / TM) * sizeof(int));
+  const size_t o_hs = take((size_t)TP * npad * npad);
   const size_t o_q = take((size_t)mpad * npad);
   const size_t o_qo = take((size_t)mpad * npad * sizeof(uint16_t));
   const size_t o_ap = take((size_t)t_groups(n) * mpad * C * C * sizeof(float));
   if (out != nullptr) {
     out->scale = (float*)(base + o_scale);
     out->Hdiag = (float*)(base + o_diag);
-    out->Hs = (_Float16*)(base + o_hs);
+    out->Cs = (uint8_t*)(base + o_cs);
+    out->Wj = (float*)(base + o_wj);
+    out->S2 = (int8_t*)(base + o_s2);
+    out->S3 = (int8_t*)(base + o_s3);
+    out->Ptile = (int*)(base + o_pt);
+    out->Hs = (int8_t*)(base + o_hs);
     out->Qp = (uint8_t*)(base + o_q);
     out->Qo = (uint16_t*)(base + o_qo);
     out->Apart = (float*)(base + o_ap);
@@ -607,17 +736,23 @@ size_t update_t_scratch_bytes(int64_t m, int64_t n, int nbits) {
   return t_layout(m, n, nbits, nullptr, nullptr);
 }
 
-// fp16 hi/lo split of the strictly lower triangle of H into scratch (once per layer).
+// integer digits of the strictly lower triangle of H and their scale factors into scratch (once
+// per layer)
 hipError_t launch_t_prepare(hipStream_t s, const float* H, int64_t m, int64_t n, int64_t ldh,
                             int nbits, void* scratch) {
   TScratch sc;
   t_layout(m, n, nbits, (char*)scratch, &sc);
   const int64_t npad = t_npad(n);
-  hipLaunchKernelGGL(maxdiag_kernel, dim3(1), dim3(256), 0, s, H, n, ldh, sc.scale, sc.Hdiag);
+  hipLaunchKernelGGL(t_diag_kernel, dim3(1), dim3(256), 0, s, H, n, ldh, npad, (int)(npad / TM), sc.scale,
+                     sc.Hdiag, sc.Cs, sc.Ptile);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(split_lower_kernel, dim3((unsigned)ceil_div(npad, 256), (unsigned)npad),
-                     dim3(256), 0, s, H, n, ldh, npad, sc.scale, sc.Hs);
+  hipLaunchKernelGGL(t_rowscale_kernel, dim3((unsigned)n), dim3(256), 0, s, H, n, ldh, sc.scale, sc.Hdiag,
+                     sc.Cs, sc.S2, sc.S3, sc.Ptile);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(t_split_kernel, dim3((unsigned)ceil_div(npad, 256), (unsigned)npad), dim3(256), 0, s,
+                     H, n, ldh, npad, sc.Cs, sc.S2, sc.S3, sc.Ptile, sc.Hs, sc.Wj);
   return hipGetLastError();
 }
 
@@ -648,7 +783,7 @@ static hipError_t launch_t_accum_n(hipStream_t s, int64_t m, int64_t n, void* sc
   }
   const int64_t total = (mpad / (TN >> NBITS)) * groups;
   hipLaunchKernelGGL(t_accum_kernel<NBITS>, dim3((unsigned)(8 * ceil_div(total, 8))), dim3(64 * TNW),
-                     shmem, s, sc.Hs, npad, sc.Qp, sc.Qo, mpad, mtiles, groups, sc.Apart);
+                     shmem, s, sc.Hs, npad, sc.Qp, sc.Qo, sc.Cs, sc.Wj, sc.Ptile, mpad, mtiles, groups, sc.Apart);
   return hipGetLastError();
 }
 
