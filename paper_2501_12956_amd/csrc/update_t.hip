@@ -46,7 +46,7 @@ constexpr float V3MAX = 8323072.f;   // with three: 2^23 - 2^16
 
 // ---- per-layer preparation ----
 // diagonal of H, column exponents e_k = clamp(EMAX + round(log2 sqrt(H_kk / max H)), 0, EMAX)
-// (stored as the one-hot value 2^e_k), two digits per tile until a row says otherwise
+// (stored as the one-hot value 2^e_k); the per-tile flags start cleared
 __global__ __launch_bounds__(256) void t_diag_kernel(const float* __restrict__ H, int64_t n,
                                                      int64_t ldh, int64_t npad, int mtiles,
                                                      float* __restrict__ scale,
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void t_diag_kernel(const float* __restrict__ H
     }
     Cs[k] = (uint8_t)(1 << e);
   }
-  for (int t = threadIdx.x; t < mtiles; t += 256) Ptile[t] = 2;
+  for (int t = threadIdx.x; t < mtiles; t += 256) Ptile[t] = 0;
   if (threadIdx.x == 0) {
     scale[0] = 1.f;
     scale[1] = 1.f;     // the fold applies the row factors; nothing is left for the solve
@@ -85,9 +85,19 @@ __global__ __launch_bounds__(256) void t_diag_kernel(const float* __restrict__ H
   }
 }
 
-// Row j: largest |H_jk| 2^-e_k and sum |H_jk| over k < j give the row exponents for two and
-// for three digits; the row asks for three digits when its scaled entries are not small
-// against the diagonal scale.
+// Flags of a tile of TM rows: some row needs three digits; some row's two-digit (three-digit)
+// integers could overflow an int32 when summed over a whole row, so the digits cannot share
+// one accumulator.
+constexpr int TF_THREE = 1, TF_SUM2 = 2, TF_SUM3 = 4;
+__device__ __host__ inline int tile_digits(int flags) { return (flags & TF_THREE) ? 3 : 2; }
+__device__ __host__ inline bool tile_shared_acc(int flags) {
+  return (flags & ((flags & TF_THREE) ? TF_SUM3 : TF_SUM2)) == 0;
+}
+
+// Row j: the largest |H_jk| 2^-e_k over k < j gives the row exponents for two and for three
+// digits; the row asks for three digits when its scaled entries are not small against the
+// diagonal scale, and sum_k |H_jk| 2^s tells whether any subset sum of the row's integers
+// (times their column factors) stays inside an int32.
 __global__ __launch_bounds__(256) void t_rowscale_kernel(const float* __restrict__ H, int64_t n,
                                                          int64_t ldh, const float* __restrict__ scale,
                                                          const float* __restrict__ Hdiag,
@@ -119,20 +129,20 @@ __global__ __launch_bounds__(256) void t_rowscale_kernel(const float* __restrict
   mx = rmx[0];
   sum = rsum[0];
   int s2 = 0, s3 = 0;
-  if (mx > 0.f && mx < __builtin_huge_valf() && sum < __builtin_huge_valf()) {
-    const int t = 29 - ilogbf(sum);                 // sum 2^t in [2^29, 2^30)
+  if (mx > 0.f && mx < __builtin_huge_valf()) {
     s2 = 14 - ilogbf(mx);
     if (ldexpf(mx, s2) > V2MAX) --s2;
     s3 = 22 - ilogbf(mx);
     if (ldexpf(mx, s3) > V3MAX) --s3;
-    s2 = s2 < t ? s2 : t;
-    s3 = s3 < t ? s3 : t;
     s2 = s2 < -120 ? -120 : (s2 > 120 ? 120 : s2);
     s3 = s3 < -120 ? -120 : (s3 > 120 ? 120 : s3);
+    // |sum_k v_jk 2^e_k [..]| <= 2^s sum_k |H_jk| + 2^(EMAX-1) n  must stay below 2^31
+    const int t = (sum < __builtin_huge_valf()) ? 29 - ilogbf(sum) : -1000;   // sum 2^t < 2^30
     const float dj = Hdiag[j];
     const bool small = dj > 0.f && dj < __builtin_huge_valf() &&
                        mx * (float)(1 << EMAX) * 16.f <= sqrtf(dj) * sqrtf(scale[2]);
-    if (!small) atomicMax(&Ptile[j / TM], 3);
+    const int flags = (small ? 0 : TF_THREE) | (s2 <= t ? 0 : TF_SUM2) | (s3 <= t ? 0 : TF_SUM3);
+    if (flags != 0) atomicOr(&Ptile[j / TM], flags);
   }
   S2[j] = (int8_t)s2;
   S3[j] = (int8_t)s3;
@@ -151,7 +161,7 @@ __global__ __launch_bounds__(256) void t_split_kernel(const float* __restrict__ 
   const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;      // column
   if (k >= npad) return;
   if (k / TM > j / TM) return;
-  const int P = Ptile[j / TM];
+  const int P = tile_digits(Ptile[j / TM]);
   const int sj = (j < n) ? ((P == 2) ? S2[j] : S3[j]) : 0;
   if (k == 0) Wj[j] = ldexpf(1.f, -sj);
   int iv = 0;
@@ -309,7 +319,9 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const int8_t* __restr
     if (half == 1 && mt == group) break;
     const int64_t jt0 = (int64_t)mt * TM;
     const int nk = (int)((jt0 + TM) / TK);    // tiles right of the diagonal are never needed (nk >= 2)
-    const int P = __builtin_amdgcn_readfirstlane(Ptile[mt]);
+    const int tflags = __builtin_amdgcn_readfirstlane(Ptile[mt]);
+    const int P = tile_digits(tflags);
+    const bool shared_acc = tile_shared_acc(tflags);   // the digits may share the accumulators
 
     auto load_q = [&](int k) {
 #pragma unroll
@@ -364,6 +376,8 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const int8_t* __restr
           acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.a[i], f.b[jn], acc[i][jn], 0, 0, 0);
     };
 
+    const int acmp = lane & (C - 1);
+
     for (int dg = 0; dg < P; ++dg) {
       int4v rsA;
       {
@@ -376,7 +390,7 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const int8_t* __restr
       auto issue = [&](int k, int st) {
         load16_to_lds(rsA, lds0 + st * T_STAGEB + wave * 1024, voff, (uint32_t)k * (uint32_t)TK);
       };
-      if (dg > 0) {
+      if (dg > 0 && shared_acc) {
         // next digit: everything so far moves up by one digit
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -426,61 +440,70 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const int8_t* __restr
       step(nk - 1, IntC<0>{}, IntC<0>{});
       // the LDS stages are reused by the next pass; slower wavefronts may still be reading
       __syncthreads();
-    }
+      if (shared_acc && dg + 1 < P) continue;
 
-    // fold: register v of tile (i, jn) is row j = i*32 + (v>>2)*8 + kh*4 + (v&3) of the tile.
-    // D[jn] = four 16 x 16 blocks (lane half, column half) of column tile jn.
-    floatx16 D[2];
+      // fold: register v of tile (i, jn) is row j = i*32 + (v>>2)*8 + kh*4 + (v&3) of the tile.
+      // D[jn] = four 16 x 16 blocks (lane half, column half) of column tile jn.  Accumulators
+      // that hold a single digit are folded with that digit's weight and start again from 0.
+      const float dgw = shared_acc ? 1.f : (dg + 1 == P ? 1.f : (dg + 2 == P ? 256.f : 65536.f));
+      const bool first_fold = half == 0 && (shared_acc || dg == 0);   // nothing stored yet
+      floatx16 D[2];
 #pragma unroll
-    for (int jn = 0; jn < 2; ++jn)
+      for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) D[jn][v] = 0.f;
-    const int acmp = lane & (C - 1);
+        for (int v = 0; v < 16; ++v) D[jn][v] = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      uint32_t qd[2][4];
-      float4 wj[4];
-#pragma unroll
-      for (int jn = 0; jn < 2; ++jn) {
-        const int il = (wave * 64 + jn * 32 + l32) >> NBITS;
-        const uint8_t* __restrict__ qr = Qp + (i0 + il) * npad + jt0 + i * 32 + kh * 4;
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) qd[jn][vq] = *reinterpret_cast<const uint32_t*>(qr + vq * 8);
-      }
-#pragma unroll
-      for (int vq = 0; vq < 4; ++vq)
-        wj[vq] = *reinterpret_cast<const float4*>(Wj + jt0 + i * 32 + kh * 4 + vq * 8);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float4 w4 = wj[v >> 2];
-        const float wv = (v & 3) == 0 ? w4.x : (v & 3) == 1 ? w4.y : (v & 3) == 2 ? w4.z : w4.w;
+      for (int i = 0; i < 4; ++i) {
+        uint32_t qd[2][4];
+        float4 wj[4];
 #pragma unroll
         for (int jn = 0; jn < 2; ++jn) {
-          const int code = (int)((qd[jn][v >> 2] >> (8 * (v & 3))) & 0xffu);
-          const float sel = (code == acmp) ? wv : 0.f;
-          D[jn] = __builtin_amdgcn_mfma_f32_16x16x1f32(sel, (float)acc[i][jn][v], D[jn], 0, 0, 0);
+          const int il = (wave * 64 + jn * 32 + l32) >> NBITS;
+          const uint8_t* __restrict__ qr = Qp + (i0 + il) * npad + jt0 + i * 32 + kh * 4;
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) qd[jn][vq] = *reinterpret_cast<const uint32_t*>(qr + vq * 8);
+        }
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          wj[vq] = *reinterpret_cast<const float4*>(Wj + jt0 + i * 32 + kh * 4 + vq * 8);
+          wj[vq].x *= dgw;
+          wj[vq].y *= dgw;
+          wj[vq].z *= dgw;
+          wj[vq].w *= dgw;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float4 w4 = wj[v >> 2];
+          const float wv = (v & 3) == 0 ? w4.x : (v & 3) == 1 ? w4.y : (v & 3) == 2 ? w4.z : w4.w;
+#pragma unroll
+          for (int jn = 0; jn < 2; ++jn) {
+            const int code = (int)((qd[jn][v >> 2] >> (8 * (v & 3))) & 0xffu);
+            const float sel = (code == acmp) ? wv : 0.f;
+            D[jn] = __builtin_amdgcn_mfma_f32_16x16x1f32(sel, (float)acc[i][jn][v], D[jn], 0, 0, 0);
+            acc[i][jn][v] = 0;
+          }
         }
       }
+      // D[jn][4 B + r] = block B = 2 * (lane half of the source) + (16-column half), element
+      // (row 4 (lane / 16) + r, column lane % 16): rows are (i', a), columns (i'', b) within the
+      // 16-column group; keep i' == i'' and add the two lane halves.  Later folds add to what this
+      // same thread stored after the first.
+#pragma unroll
+      for (int jn = 0; jn < 2; ++jn)
+#pragma unroll
+        for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int mrow = 4 * (lane >> 4) + r, ncol = lane & 15;
+            if ((mrow >> NBITS) != (ncol >> NBITS)) continue;
+            float v = D[jn][4 * ch + r] + D[jn][4 * (2 + ch) + r];
+            const int col = wave * 64 + jn * 32 + ch * 16 + ncol;      // (row i, code b) pair of the slab
+            const int il = col >> NBITS, bb = col & (C - 1), aa = mrow & (C - 1);
+            float* dst = Apart + ((int64_t)group * mpad + i0 + il) * C * C + aa * C + bb;
+            if (!first_fold) v += *dst;
+            *dst = v;
+          }
     }
-    // D[jn][4 B + r] = block B = 2 * (lane half of the source) + (16-column half), element
-    // (row 4 (lane / 16) + r, column lane % 16): rows are (i', a), columns (i'', b) within the
-    // 16-column group; keep i' == i'' and add the two lane halves.  The second row tile adds
-    // to what this same thread stored after the first.
-#pragma unroll
-    for (int jn = 0; jn < 2; ++jn)
-#pragma unroll
-      for (int ch = 0; ch < 2; ++ch)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int mrow = 4 * (lane >> 4) + r, ncol = lane & 15;
-          if ((mrow >> NBITS) != (ncol >> NBITS)) continue;
-          float v = D[jn][4 * ch + r] + D[jn][4 * (2 + ch) + r];
-          const int col = wave * 64 + jn * 32 + ch * 16 + ncol;      // (row i, code b) pair of the slab
-          const int il = col >> NBITS, bb = col & (C - 1), aa = mrow & (C - 1);
-          float* dst = Apart + ((int64_t)group * mpad + i0 + il) * C * C + aa * C + bb;
-          if (half == 1) v += *dst;
-          *dst = v;
-        }
   }
 }
 

@@ -242,6 +242,44 @@ def test_update_T_stagewise(ctx, m, n, nbits):
     assert np.array_equal(cnt.cpu().numpy(), cref)
 
 
+def _structured_H(kind, n, seed):
+    """Second-moment matrices that drive the integer representation of H in the T-update through
+    its cases: weakly or strongly correlated features (two or three digits per entry), feature
+    scales far beyond the range of the column factors, both kinds of rows in one matrix, and a
+    feature that is never active."""
+    rng = np.random.default_rng(seed)
+    p = 4096
+    Z = rng.standard_normal((n, p))
+    f = rng.standard_normal((1, p))
+    rho = {"weak": 0.0, "medium": 0.4, "strong": 0.8, "wide": 0.0, "mixed": 0.0, "dead": 0.3}[kind]
+    X = np.sqrt(1 - rho) * Z + np.sqrt(rho) * f
+    d = np.exp(rng.uniform(np.log(0.5), np.log(8.0), size=n))
+    if kind == "wide":
+        d = np.exp(rng.uniform(np.log(1e-2), np.log(1e3), size=n))
+    if kind == "mixed":
+        X[n // 2:] = np.sqrt(0.1) * Z[n // 2:] + np.sqrt(0.9) * f
+    if kind == "dead":
+        d[n // 3] = 0.0
+    X = X * d[:, None]
+    return (X @ X.T).astype(np.float32)
+
+
+@pytest.mark.parametrize("kind,nbits,m,n", [(k, b, 40, 300) for b in (3, 4)
+                                            for k in ("weak", "strong", "wide", "mixed", "dead")]
+                         + [("medium", 4, 16, 1100), ("mixed", 3, 70, 1100), ("weak", 2, 130, 700)])
+def test_update_T_structured_H(ctx, kind, nbits, m, n):
+    H32 = _structured_H(kind, n, 11)
+    rng = np.random.default_rng(12)
+    W = (rng.standard_normal((m, n)) * 0.02).astype(np.float32)
+    Q = rng.integers(0, 1 << nbits, size=(m, n)).astype(np.uint8)
+    Tg = ctx.update_T(dev(W), dev(H32), dev(Q), dev(np.zeros((m, 1 << nbits), np.float32)), nbits)
+    Tg = (Tg[0] if isinstance(Tg, tuple) else Tg).cpu().numpy().astype(np.float64)
+    Tref, _ = ref.update_T(W.astype(np.float64), H32.astype(np.float64), Q, nbits)
+    err = np.abs(Tg - Tref).max(axis=1) / np.abs(Tref).max(axis=1)
+    print("T-update, %s H %dx%d, N=%d: max row error %.2e" % (kind, m, n, nbits, err.max()))
+    assert np.all(err <= 1e-4)
+
+
 def test_update_T_empty_codes(ctx):
     from paper_2501_12956_amd import binding as b
     m, n, nbits = 6, 96, 3
