@@ -42,16 +42,16 @@ PEAK_F32_ADD_TOPS = 78.6
 # reading of a plain 1 GiB copy: x2.000 and x1.000); copied from profiles/bench_c3_hbm_traffic.txt,
 # which gives the commands.  Other configs report null.
 TRAFFIC_C3_BYTES = {
-    "hessian": (13128.79 + 580.15) * 2 ** 20,     # product kernel + reduction
-    "update_s": 1995.05 * 2 ** 20,
-    "t_accum": 820.07 * 2 ** 20,
-    "t_solve": 145.10 * 2 ** 20,
+    "hessian": (12779.74 + 580.15) * 2 ** 20,     # product kernel + reduction
+    "update_s": 1949.42 * 2 ** 20,
+    "t_accum": 1127.82 * 2 ** 20,
+    "t_solve": 145.09 * 2 ** 20,
     "t_pad": 64.02 * 2 ** 20,
-    "gemm_wh": (951.10 + 2 * 64.10 + 2 * 128.01) * 2 ** 20,     # piece product + 2 x (absmax, split)
-    "loss": (951.10 + 2 * 64.10 + 2 * 128.01 + 146.03 + 128.15) * 2 ** 20,
-    "init": (96.02 + 64.33) * 2 ** 20,
-    "cholesky": (128.34 + 15 * 34.82 + 64 * 2.27) * 2 ** 20,
-    "t_prep": (65.24 + 0.52) * 2 ** 20,
+    "gemm_wh": (930.41 + 2 * 64.10 + 2 * 128.01) * 2 ** 20,     # piece product + 2 x (absmax, split)
+    "loss": (930.41 + 2 * 64.10 + 2 * 128.01 + 146.03 + 128.15) * 2 ** 20,
+    "init": (96.03 + 64.34) * 2 ** 20,
+    "cholesky": (128.34 + 15 * 34.91 + 64 * 2.27) * 2 ** 20,
+    "t_prep": (0.54 + 32.75 + 48.81) * 2 ** 20,   # diagonal, row scales, digits
 }
 
 
@@ -71,7 +71,7 @@ def kernel_work(cls, m, n, p, nbits, iters):
     if cls == "loss":
         return "mfma", 2.0 * m * n * n, "TFLOP/s", PEAK_F16_TFLOPS
     if cls == "t_prep":
-        return "hbm", 4.0 * n * n / 2 + 4.0 * n * n / 2, "GB/s", PEAK_HBM_GBS  # read tril(H), write 2 fp16 halves
+        return "hbm", 2 * 4.0 * n * n / 2 + 2.0 * n * n / 2, "GB/s", PEAK_HBM_GBS  # read tril(H) twice, write 2 digits
     if cls == "t_pad":
         return "hbm", 2.0 * m * n, "GB/s", PEAK_HBM_GBS
     if cls == "t_solve":

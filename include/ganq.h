@@ -152,7 +152,11 @@ ganq_status ganq_update_S(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, i
  * row, S_i the one-hot form of Q_i.  H is the raw X X^T (n x n fp32,
  * symmetric; both triangles are read).  T holds T^k on entry (used only by
  * GANQ_EMPTY_KEEP) and T^{k+1} on return.  empty_count (optional, m int32)
- * receives the number of unused or numerically dependent codes per row. */
+ * receives the number of unused or numerically dependent codes per row.
+ * The off-diagonal entries of H enter S_i H S_i^T as integers of 16 bits
+ * (rows whose entries are below 1/16 of sqrt(H_jj max_k H_kk)) or 24 bits,
+ * scaled per row and per column by powers of two and summed exactly; the
+ * diagonal and W H are taken in fp32 and the solve runs in float64. */
 ganq_status ganq_update_T(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
                           const float* H, int64_t ldh, const uint8_t* Q, int64_t ldq, int nbits,
                           ganq_empty empty, float* T, int32_t* empty_count);
@@ -239,7 +243,7 @@ typedef enum {
   GANQ_K_INIT = 2,     /* T^0 (and fp16 -> fp32 conversion of W) */
   GANQ_K_GEMM_WH = 3,  /* G = W H, once per layer */
   GANQ_K_UPDATE_S = 4, /* one S-update sweep (one launch) */
-  GANQ_K_T_PREP = 5,   /* fp16 split of H, once per layer */
+  GANQ_K_T_PREP = 5,   /* integer digits of H for the T-update, once per layer */
   GANQ_K_T_PAD = 6,    /* padded copy of Q, once per sweep */
   GANQ_K_T_ACCUM = 7,  /* one-hot GEMM of the T-update, once per sweep */
   GANQ_K_T_SOLVE = 8,  /* per-row assembly and solve, once per sweep */
