@@ -286,20 +286,27 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const int8_t* __restr
   // next one; the stage written for step s held step s - 3 (stages rotate over all steps of
   // the workgroup, across digits and row tiles), so its entries are cleared with q3.  Before
   // the first steps the "old" positions are this thread's own code-0 positions (zeros already).
+  // With few bits per index a thread owns many positions and that queue would not fit the
+  // register file: the wavefront then zeroes its part of the tile with full-width stores
+  // instead (the rows (il, code) of its threads are 64 consecutive rows of the tile, 4 KB that
+  // no other wavefront writes, and the LDS operations of one wavefront execute in order).
+  constexpr bool QUEUE = NBITS >= 3;
+  constexpr int QW = QUEUE ? EW : 1;
   const int ex_il = (tid * EPT) / TK, ex_kk0 = (tid * EPT) % TK;
   const uint32_t* __restrict__ qorow = reinterpret_cast<const uint32_t*>(Qo + (i0 + ex_il) * npad + ex_kk0);
   const uint32_t* __restrict__ csrow = reinterpret_cast<const uint32_t*>(Cs + ex_kk0);
-  uint32_t q3[EW], q2[EW], q1[EW], q0[EW], cv[CW];
+  uint32_t q3[QW], q2[QW], q1[QW], q0[EW], cv[CW];
+  if constexpr (QUEUE) {
 #pragma unroll
-  for (int w = 0; w < EW; ++w) {
-    uint32_t pk = 0;
+    for (int w = 0; w < EW; ++w) {
+      uint32_t pk = 0;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int nrow = ex_il * C, kk = ex_kk0 + 2 * w + h;
-      pk |= (uint32_t)(nrow * T_ROWB + ((((kk >> 4) ^ (nrow >> 1)) & 3) << 4) + (kk & 15)) << (16 * h);
+      for (int h = 0; h < 2; ++h) {
+        const int nrow = ex_il * C, kk = ex_kk0 + 2 * w + h;
+        pk |= (uint32_t)(nrow * T_ROWB + ((((kk >> 4) ^ (nrow >> 1)) & 3) << 4) + (kk & 15)) << (16 * h);
+      }
+      q3[w] = q2[w] = q1[w] = pk;
     }
-    q3[w] = q2[w] = q1[w] = pk;
-    q0[w] = pk;
   }
 
   // direct load of the A tile: one instruction covers 16 rows x 64 bytes, one per wavefront
@@ -329,21 +336,30 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const int8_t* __restr
 #pragma unroll
       for (int w = 0; w < CW; ++w) cv[w] = csrow[(k * TK) / 4 + w];
     };
-    // clear the entries of the step that used this stage last (q3), set those of q0, rotate
+    // clear the entries of the step that used this stage last (q3, or the whole part of this
+    // wavefront), set those of q0, rotate
     auto scatter = [&](int st) {
       unsigned char* Bs = smem + st * T_STAGEB + T_ATILEB;
+      if constexpr (QUEUE) {
 #pragma unroll
-      for (int w = 0; w < EW; ++w) {
-        Bs[q3[w] & 0xffffu] = 0;
-        Bs[q3[w] >> 16] = 0;
+        for (int w = 0; w < EW; ++w) {
+          Bs[q3[w] & 0xffffu] = 0;
+          Bs[q3[w] >> 16] = 0;
+        }
+      } else {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          *reinterpret_cast<uint4*>(Bs + wave * 4096 + t * 1024 + lane * 16) = uint4{0u, 0u, 0u, 0u};
       }
 #pragma unroll
       for (int w = 0; w < EW; ++w) {
         Bs[q0[w] & 0xffffu] = (unsigned char)((cv[w >> 1] >> (16 * (w & 1))) & 0xffu);
         Bs[q0[w] >> 16] = (unsigned char)((cv[w >> 1] >> (16 * (w & 1) + 8)) & 0xffu);
-        q3[w] = q2[w];
-        q2[w] = q1[w];
-        q1[w] = q0[w];
+        if constexpr (QUEUE) {
+          q3[w] = q2[w];
+          q2[w] = q1[w];
+          q1[w] = q0[w];
+        }
       }
     };
 
