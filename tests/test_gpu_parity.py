@@ -280,6 +280,33 @@ def test_update_T_structured_H(ctx, kind, nbits, m, n):
     assert np.all(err <= 1e-4)
 
 
+def test_update_T_magnitude_and_diagonal_H(ctx):
+    """The codebooks do not depend on the scale of H: a power-of-two factor moves the row exponents
+    of the integer representation and nothing else.  And a diagonal H (no off-diagonal digits at
+    all) gives the H_jj-weighted mean of each group."""
+    m, n, nbits = 24, 300, 4
+    H32 = _structured_H("mixed", n, 3)
+    rng = np.random.default_rng(4)
+    W = (rng.standard_normal((m, n)) * 0.02).astype(np.float32)
+    Q = rng.integers(0, 1 << nbits, size=(m, n)).astype(np.uint8)
+    T0 = dev(np.zeros((m, 1 << nbits), np.float32))
+    base = ctx.update_T(dev(W), dev(H32), dev(Q), T0.clone(), nbits).cpu().numpy()
+    for e in (-60, 45):
+        Hs = np.ldexp(H32, e).astype(np.float32)
+        assert np.isfinite(Hs).all() and Hs.min() != 0
+        got = ctx.update_T(dev(W), dev(Hs), dev(Q), T0.clone(), nbits).cpu().numpy()
+        assert np.abs(got - base).max() <= 1e-6 * np.abs(base).max(), e
+    d = rng.uniform(0.5, 4.0, size=n).astype(np.float32)
+    got = ctx.update_T(dev(W), dev(np.diag(d)), dev(Q), T0.clone(), nbits).cpu().numpy().astype(np.float64)
+    want = np.zeros_like(got)
+    for i in range(m):
+        for c in range(1 << nbits):
+            sel = Q[i] == c
+            if sel.any():
+                want[i, c] = (W[i, sel].astype(np.float64) * d[sel]).sum() / d[sel].astype(np.float64).sum()
+    assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
+
+
 def test_update_T_empty_codes(ctx):
     from paper_2501_12956_amd import binding as b
     m, n, nbits = 6, 96, 3
