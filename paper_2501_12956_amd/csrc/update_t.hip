@@ -15,13 +15,16 @@
 // with a power-of-two column factor 2^e_k (e_k = 0..6, from the diagonal, so that a row's
 // entries use the same digits whether their column is large or small; it is the value of
 // the one-hot entry, which an int8 operand can hold) and a power-of-two row factor chosen
-// so that the row's largest |v| fills the digits and sum_k |v_jk| 2^e_k < 2^30 (no subset
-// sum can overflow an int32).  v is split into balanced base-256 digits, one GEMM pass per
-// digit from the top, the accumulators shifted left by 8 between passes, so the accumulator
-// ends as sum_k v_jk 2^e_k [Q_ik == b] exactly.  A tile of 128 rows takes two digits when
-// every row's scaled off-diagonal entries stay below 1/16 of the diagonal scale
-// sqrt(H_jj max_k H_kk) - the absolute error of an entry is then at most that of 20-bit
-// digits on a fully correlated row - and three digits otherwise.
+// so that the row's largest |v| fills the digits.  v is split into balanced base-256 digits,
+// one GEMM pass per digit from the top.  Where sum_k |v_jk| 2^e_k < 2^30 for every row of a
+// tile of 128 rows (no subset sum can overflow an int32) the digits share the accumulators,
+// shifted left by 8 between passes, which end as sum_k v_jk 2^e_k [Q_ik == b] exactly;
+// elsewhere each digit is folded on its own.  A tile takes two digits when, for every row,
+// 16 times the largest scaled entry stays below sqrt(H_jj) g, g the smallest
+// sqrt(H_kk) 2^-e_k over the live columns (about sqrt(max H) / 64 when the columns' scales
+// span less than the 2^6 the column factors cover; never taken below 2^-10 sqrt(max H)):
+// the absolute error of an entry is then at most 2^-20 sqrt(H_jj H_kk), that of 20-bit
+// digits on a fully correlated row.  Otherwise it takes three digits.
 // Only k < j is visited (H is symmetric):
 //   M_i[a, b] = sum_j [Q_ij == a] Z[j, (i,b)],   A_i = M_i + M_i^T + Diag(D_i),
 //   D_i[a] = sum_{j: Q_ij == a} H_jj.
@@ -66,6 +69,10 @@ __global__ __launch_bounds__(256) void t_diag_kernel(const float* __restrict__ H
     __syncthreads();
   }
   const float hmax = red[0];
+  __syncthreads();
+  // g = smallest sqrt(H_kk) 2^-e_k over the live columns: what one unit of a column's integers
+  // is worth relative to that column's own scale
+  float gmin = __builtin_huge_valf();
   for (int64_t k = threadIdx.x; k < npad; k += 256) {
     int e = 0;
     if (k < n && hmax > 0.f) {
@@ -73,15 +80,26 @@ __global__ __launch_bounds__(256) void t_diag_kernel(const float* __restrict__ H
       if (d > 0.f && d < __builtin_huge_valf()) {
         const float t = (float)EMAX + rintf(0.5f * log2f(d / hmax));
         e = t < 0.f ? 0 : (t > (float)EMAX ? EMAX : (int)t);
+        gmin = fminf(gmin, sqrtf(d) / (float)(1 << e));
       }
     }
     Cs[k] = (uint8_t)(1 << e);
   }
+  red[threadIdx.x] = gmin;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] = fminf(red[threadIdx.x], red[threadIdx.x + w]);
+    __syncthreads();
+  }
+  gmin = red[0];
   for (int t = threadIdx.x; t < mtiles; t += 256) Ptile[t] = 0;
   if (threadIdx.x == 0) {
     scale[0] = 1.f;
     scale[1] = 1.f;     // the fold applies the row factors; nothing is left for the solve
     scale[2] = hmax;
+    // columns more than 2^10 below the largest one are held to its absolute precision only
+    const float gfloor = ldexpf(sqrtf(hmax), -10);
+    scale[3] = (gmin < __builtin_huge_valf() && gmin > gfloor) ? gmin : gfloor;
   }
 }
 
@@ -95,8 +113,9 @@ __device__ __host__ inline bool tile_shared_acc(int flags) {
 }
 
 // Row j: the largest |H_jk| 2^-e_k over k < j gives the row exponents for two and for three
-// digits; the row asks for three digits when its scaled entries are not small against the
-// diagonal scale, and sum_k |H_jk| 2^s tells whether any subset sum of the row's integers
+// digits; the row asks for three digits unless 16 of its largest scaled entry stay below
+// sqrt(H_jj) g (a unit of its 16-bit integers is then at most 2^-19 sqrt(H_jj H_kk) for
+// every live column k), and sum_k |H_jk| 2^s tells whether any subset sum of the row's integers
 // (times their column factors) stays inside an int32.
 __global__ __launch_bounds__(256) void t_rowscale_kernel(const float* __restrict__ H, int64_t n,
                                                          int64_t ldh, const float* __restrict__ scale,
@@ -139,8 +158,7 @@ __global__ __launch_bounds__(256) void t_rowscale_kernel(const float* __restrict
     // |sum_k v_jk 2^e_k [..]| <= 2^s sum_k |H_jk| + 2^(EMAX-1) n  must stay below 2^31
     const int t = (sum < __builtin_huge_valf()) ? 29 - ilogbf(sum) : -1000;   // sum 2^t < 2^30
     const float dj = Hdiag[j];
-    const bool small = dj > 0.f && dj < __builtin_huge_valf() &&
-                       mx * (float)(1 << EMAX) * 16.f <= sqrtf(dj) * sqrtf(scale[2]);
+    const bool small = dj > 0.f && dj < __builtin_huge_valf() && mx * 16.f <= sqrtf(dj) * scale[3];
     const int flags = (small ? 0 : TF_THREE) | (s2 <= t ? 0 : TF_SUM2) | (s3 <= t ? 0 : TF_SUM3);
     if (flags != 0) atomicOr(&Ptile[j / TM], flags);
   }

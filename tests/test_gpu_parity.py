@@ -266,7 +266,8 @@ def _structured_H(kind, n, seed):
 
 @pytest.mark.parametrize("kind,nbits,m,n", [(k, b, 40, 300) for b in (3, 4)
                                             for k in ("weak", "strong", "wide", "mixed", "dead")]
-                         + [("medium", 4, 16, 1100), ("mixed", 3, 70, 1100), ("weak", 2, 130, 700)])
+                         + [("medium", 4, 16, 1100), ("mixed", 3, 70, 1100), ("weak", 2, 130, 700),
+                            ("wide", 2, 168, 43), ("wide", 1, 60, 90)])
 def test_update_T_structured_H(ctx, kind, nbits, m, n):
     H32 = _structured_H(kind, n, 11)
     rng = np.random.default_rng(12)
