@@ -153,10 +153,12 @@ ganq_status ganq_update_S(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, i
  * symmetric; both triangles are read).  T holds T^k on entry (used only by
  * GANQ_EMPTY_KEEP) and T^{k+1} on return.  empty_count (optional, m int32)
  * receives the number of unused or numerically dependent codes per row.
- * The off-diagonal entries of H enter S_i H S_i^T as integers of 16 bits
- * (rows whose entries are below 1/16 of sqrt(H_jj max_k H_kk)) or 24 bits,
- * scaled per row and per column by powers of two and summed exactly; the
- * diagonal and W H are taken in fp32 and the solve runs in float64. */
+ * The off-diagonal entries of H enter S_i H S_i^T as integers of 16, 24 or
+ * 32 bits, scaled per row and per column by powers of two and summed
+ * exactly; the width is the smallest for which one unit is at most
+ * 2^-19 sqrt(H_jj H_kk) (features more than 2^18 below the largest one are
+ * measured against that floor).  The diagonal and W H are taken in fp32 and
+ * the solve runs in float64. */
 ganq_status ganq_update_T(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
                           const float* H, int64_t ldh, const uint8_t* Q, int64_t ldq, int nbits,
                           ganq_empty empty, float* T, int32_t* empty_count);

@@ -11,7 +11,7 @@
 // right operand is the one-hot expansion of Q, kept in LDS and updated in place
 // from precomputed positions.  It runs in integer arithmetic on
 // v_mfma_i32_32x32x32_i8 (twice the fp16 rate, exact accumulation):
-//   H_jk ~ v_jk 2^(e_k - s_j),  v_jk an integer of 16 or 24 bits,
+//   H_jk ~ v_jk 2^(e_k - s_j),  v_jk an integer of 16, 24 or 32 bits,
 // with a power-of-two column factor 2^e_k (e_k = 0..6, from the diagonal, so that a row's
 // entries use the same digits whether their column is large or small; it is the value of
 // the one-hot entry, which an int8 operand can hold) and a power-of-two row factor chosen
@@ -22,9 +22,10 @@
 // elsewhere each digit is folded on its own.  A tile takes two digits when, for every row,
 // 16 times the largest scaled entry stays below sqrt(H_jj) g, g the smallest
 // sqrt(H_kk) 2^-e_k over the live columns (about sqrt(max H) / 64 when the columns' scales
-// span less than the 2^6 the column factors cover; never taken below 2^-10 sqrt(max H)):
+// span less than the 2^6 the column factors cover; never taken below 2^-18 sqrt(max H)):
 // the absolute error of an entry is then at most 2^-20 sqrt(H_jj H_kk), that of 20-bit
-// digits on a fully correlated row.  Otherwise it takes three digits.
+// digits on a fully correlated row.  Otherwise it takes three digits, or four where the same
+// bound needs them (feature scales spread over more than 2^10).
 // Only k < j is visited (H is symmetric):
 //   M_i[a, b] = sum_j [Q_ij == a] Z[j, (i,b)],   A_i = M_i + M_i^T + Diag(D_i),
 //   D_i[a] = sum_{j: Q_ij == a} H_jj.
@@ -42,10 +43,10 @@ constexpr int TM = 128;    // rows j of H per tile
 constexpr int TN = 512;    // (row i, code b) pairs per workgroup
 constexpr int TK = 64;     // k per stage
 constexpr int TNW = 8;     // wavefronts per workgroup, each 128 x 64 of the tile
-constexpr int TP = 3;      // most base-256 digits per entry
+constexpr int TP = 4;      // most base-256 digits per entry
 constexpr int EMAX = 6;    // largest column exponent (the one-hot entry 2^e is an int8)
 constexpr float V2MAX = 32512.f;     // largest |v| with two digits:  127 * 256 + 127 - 127
-constexpr float V3MAX = 8323072.f;   // with three: 2^23 - 2^16
+constexpr float V3MAX = 8323072.f;   // with three: 2^23 - 2^16 (four: 256 times that, 2^31 - 2^24)
 
 // ---- per-layer preparation ----
 // diagonal of H, column exponents e_k = clamp(EMAX + round(log2 sqrt(H_kk / max H)), 0, EMAX)
@@ -97,8 +98,8 @@ __global__ __launch_bounds__(256) void t_diag_kernel(const float* __restrict__ H
     scale[0] = 1.f;
     scale[1] = 1.f;     // the fold applies the row factors; nothing is left for the solve
     scale[2] = hmax;
-    // columns more than 2^10 below the largest one are held to its absolute precision only
-    const float gfloor = ldexpf(sqrtf(hmax), -10);
+    // columns more than 2^18 below the largest one are held to its absolute precision only
+    const float gfloor = ldexpf(sqrtf(hmax), -18);
     scale[3] = (gmin < __builtin_huge_valf() && gmin > gfloor) ? gmin : gfloor;
   }
 }
@@ -106,9 +107,12 @@ __global__ __launch_bounds__(256) void t_diag_kernel(const float* __restrict__ H
 // Flags of a tile of TM rows: some row needs three digits; some row's two-digit (three-digit)
 // integers could overflow an int32 when summed over a whole row, so the digits cannot share
 // one accumulator.
-constexpr int TF_THREE = 1, TF_SUM2 = 2, TF_SUM3 = 4;
-__device__ __host__ inline int tile_digits(int flags) { return (flags & TF_THREE) ? 3 : 2; }
+constexpr int TF_THREE = 1, TF_SUM2 = 2, TF_SUM3 = 4, TF_FOUR = 8;
+__device__ __host__ inline int tile_digits(int flags) {
+  return (flags & TF_FOUR) ? 4 : (flags & TF_THREE) ? 3 : 2;
+}
 __device__ __host__ inline bool tile_shared_acc(int flags) {
+  if (flags & TF_FOUR) return false;
   return (flags & ((flags & TF_THREE) ? TF_SUM3 : TF_SUM2)) == 0;
 }
 
@@ -153,13 +157,17 @@ __global__ __launch_bounds__(256) void t_rowscale_kernel(const float* __restrict
     if (ldexpf(mx, s2) > V2MAX) --s2;
     s3 = 22 - ilogbf(mx);
     if (ldexpf(mx, s3) > V3MAX) --s3;
-    s2 = s2 < -120 ? -120 : (s2 > 120 ? 120 : s2);
-    s3 = s3 < -120 ? -120 : (s3 > 120 ? 120 : s3);
+    s2 = s2 < -120 ? -120 : (s2 > 110 ? 110 : s2);
+    s3 = s3 < -120 ? -120 : (s3 > 110 ? 110 : s3);     // four digits use s3 + 8
     // |sum_k v_jk 2^e_k [..]| <= 2^s sum_k |H_jk| + 2^(EMAX-1) n  must stay below 2^31
     const int t = (sum < __builtin_huge_valf()) ? 29 - ilogbf(sum) : -1000;   // sum 2^t < 2^30
     const float dj = Hdiag[j];
-    const bool small = dj > 0.f && dj < __builtin_huge_valf() && mx * 16.f <= sqrtf(dj) * scale[3];
-    const int flags = (small ? 0 : TF_THREE) | (s2 <= t ? 0 : TF_SUM2) | (s3 <= t ? 0 : TF_SUM3);
+    const bool dok = dj > 0.f && dj < __builtin_huge_valf();
+    const float yard = dok ? sqrtf(dj) * scale[3] : 0.f;
+    const bool two = dok && mx * 16.f <= yard;      // a unit of 16-bit integers is small enough
+    const bool three = dok && mx <= 16.f * yard;    // a unit of 24-bit integers is
+    const int flags = (two ? 0 : TF_THREE) | (three ? 0 : TF_FOUR) | (s2 <= t ? 0 : TF_SUM2) |
+                      (s3 <= t ? 0 : TF_SUM3);
     if (flags != 0) atomicOr(&Ptile[j / TM], flags);
   }
   S2[j] = (int8_t)s2;
@@ -180,11 +188,11 @@ __global__ __launch_bounds__(256) void t_split_kernel(const float* __restrict__ 
   if (k >= npad) return;
   if (k / TM > j / TM) return;
   const int P = tile_digits(Ptile[j / TM]);
-  const int sj = (j < n) ? ((P == 2) ? S2[j] : S3[j]) : 0;
+  const int sj = (j < n) ? ((P == 2) ? S2[j] : (P == 3) ? S3[j] : S3[j] + 8) : 0;
   if (k == 0) Wj[j] = ldexpf(1.f, -sj);
   int iv = 0;
   if (j < n && k < j) {
-    const float lim = (P == 2) ? V2MAX : V3MAX;
+    const float lim = (P == 2) ? V2MAX : (P == 3) ? V3MAX : 256.f * V3MAX;
     float v = rintf(ldexpf(H[j * ldh + k], sj) / (float)Cs[k]);
     v = (v == v) ? fminf(fmaxf(v, -lim), lim) : 0.f;
     iv = (int)v;
@@ -197,9 +205,18 @@ __global__ __launch_bounds__(256) void t_split_kernel(const float* __restrict__ 
     Hs[ps + o] = (int8_t)d0;
   } else {
     const int d1 = (int)(int8_t)(v1 & 0xff);
-    Hs[o] = (int8_t)((v1 - d1) >> 8);
-    Hs[ps + o] = (int8_t)d1;
-    Hs[2 * ps + o] = (int8_t)d0;
+    const int v2 = (v1 - d1) >> 8;
+    if (P == 3) {
+      Hs[o] = (int8_t)v2;
+      Hs[ps + o] = (int8_t)d1;
+      Hs[2 * ps + o] = (int8_t)d0;
+    } else {
+      const int d2 = (int)(int8_t)(v2 & 0xff);
+      Hs[o] = (int8_t)((v2 - d2) >> 8);
+      Hs[ps + o] = (int8_t)d2;
+      Hs[2 * ps + o] = (int8_t)d1;
+      Hs[3 * ps + o] = (int8_t)d0;
+    }
   }
 }
 
@@ -479,7 +496,7 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const int8_t* __restr
       // fold: register v of tile (i, jn) is row j = i*32 + (v>>2)*8 + kh*4 + (v&3) of the tile.
       // D[jn] = four 16 x 16 blocks (lane half, column half) of column tile jn.  Accumulators
       // that hold a single digit are folded with that digit's weight and start again from 0.
-      const float dgw = shared_acc ? 1.f : (dg + 1 == P ? 1.f : (dg + 2 == P ? 256.f : 65536.f));
+      const float dgw = shared_acc ? 1.f : ldexpf(1.f, 8 * (P - 1 - dg));
       const bool first_fold = half == 0 && (shared_acc || dg == 0);   // nothing stored yet
       floatx16 D[2];
 #pragma unroll
