@@ -222,6 +222,35 @@ def test_update_S_ties_and_identity(ctx):
     assert list(Q[0]) == [0, 1, 0, 0, 1] and list(Q[1]) == [0, 0, 0, 2, 2]
 
 
+def test_updates_on_strided_views(ctx):
+    """W, L, H and Q as views with leading dimensions larger than n, L additionally starting at an
+    address that is only 4-byte aligned (the S-update then fetches L element by element): same
+    indices and codebooks as the contiguous calls, bit for bit."""
+    m, n, nbits = 37, 900, 4
+    W, X = make_problem(m, n, 4 * n, nbits, seed=9)
+    H64 = ref.build_hessian(X.numpy())
+    L32 = torch.from_numpy(ref.cholesky(H64)[0]).float().cuda()
+    H32 = torch.from_numpy(H64).float().cuda()
+    T32 = torch.from_numpy(ref.init_codebooks(W.numpy(), nbits)).float().cuda()
+    Wg = W.cuda()
+    Q0 = ctx.update_S(Wg, L32, T32, nbits)
+    T0 = ctx.update_T(Wg, H32, Q0, T32.clone(), nbits)
+
+    def wide(t, pad, shift=0):
+        big = torch.zeros(t.shape[0], t.shape[1] + pad + shift, dtype=t.dtype, device="cuda")
+        view = big[:, shift:shift + t.shape[1]]
+        view.copy_(t)
+        return view
+
+    Wv, Lv, Hv = wide(Wg, 12), wide(L32, 6, shift=1), wide(H32, 20)
+    assert Lv.data_ptr() % 16 != 0 and Lv.stride(0) % 4 != 0
+    Qv = wide(torch.zeros_like(Q0), 5)
+    ctx.update_S(Wv, Lv, T32, nbits, Q=Qv)
+    assert torch.equal(Qv, Q0)
+    T1 = ctx.update_T(Wv, Hv, Qv, T32.clone(), nbits)
+    assert torch.equal(T1, T0)
+
+
 # ----------------------------------------------------------------------------- T-update
 @pytest.mark.parametrize("m,n,nbits", [(40, 200, 4), (16, 64, 3), (33, 300, 4), (3, 130, 1), (20, 257, 2),
                                        (2, 1, 2)])
