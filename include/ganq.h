@@ -192,8 +192,10 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
 
 /* Outlier split W = W_sparse + W_dense (Appendix B, Algorithm 2; Section 3.3).
  * With p = 1 - r/2, per row the cut-offs are the values at sorted positions
- * lower = ceil(n (1 - p)) and upper = min(floor(n p), n - 1) (positions computed
- * in double exactly as written); entries >= the upper or <= the lower cut-off
+ * lower = ceil(n (1 - p)) and upper = min(floor(n p), n - 1), evaluated as the
+ * real-number expressions ceil(n r / 2) and floor(n - n r / 2) (n r / 2 within
+ * 1e-9 relative of an integer counts as that integer, so n = 2000, r = 0.01
+ * cuts at positions 10 and 1990); entries >= the upper or <= the lower cut-off
  * are outliers.  W is m x n fp16 or fp32; W_dense is m x n fp32 with zeros at
  * the outlier positions and feeds ganq_quantize_layer unchanged.  W_sparse is
  * returned as CSR: row_ptr (m + 1 entries, int64), col_idx and values (columns

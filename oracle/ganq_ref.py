@@ -22,6 +22,8 @@ Pinned (see the CPU test-suite):
   layer_loss      three algebraically equal forms, Eq. (1), (9), (13)
   quantize_layer  half-step monotonicity of the T-step, restartability,
                   scaling invariances
+  outlier_split   hand-worked rows where floor/ceil and +-1 of either cut-off
+                  position change the result; integer n r / 2 cases
   lut_storage_fraction   Table 1 printed percentages
   pack_codes      hand-written byte patterns, round trip, Table 1 byte counts
   lut_matvec      unit vectors pick single table entries, constant tables give
@@ -314,17 +316,32 @@ def quantize_layer(W, H, T0, nbits, iters, L=None, precond=PRECOND_NONE, lam=0.0
 # --------------------------------------------------------------------------
 # Outlier split                                   Appendix B, Algorithm 2
 # --------------------------------------------------------------------------
+def outlier_cutoff_positions(n, r):
+    """Sorted positions (lower, upper) of the two cut-offs of Algorithm 2:
+    lower = ceil(n (1 - p)) and upper = floor(n p) with p = 1 - r/2, i.e.
+    ceil(n r / 2) and floor(n - n r / 2) as real-number expressions.  They are
+    evaluated from x = n r / 2 so that 1 - (1 - r/2) is never formed in floating
+    point, and x is taken as an integer when it is one up to rounding (within
+    1e-9 relative): n = 2000, r = 0.01 gives positions 10 and 1990.  The upper
+    position is clamped to n - 1 (r = 0 would index past the row)."""
+    x = n * (0.5 * r)
+    k = float(np.round(x))
+    if abs(x - k) <= 1e-9 * max(1.0, abs(x)):
+        x = k
+    lower = int(np.ceil(x))
+    upper = min(int(np.floor(n - x)), n - 1)
+    return lower, upper
+
+
 def outlier_split(W, r):
     """W = W_sparse + W_dense, Algorithm 2: per row, entries at or beyond the
-    symmetric tail cut-offs (sorted positions floor(n p) and ceil(n (1 - p)),
-    p = 1 - r/2; comparisons are >= and <=) go to W_sparse, the rest to
-    W_dense.  The upper position is clamped to n - 1.
+    symmetric tail cut-offs (the values at the sorted positions of
+    outlier_cutoff_positions; comparisons are >= and <=) go to W_sparse, the
+    rest to W_dense.
     """
     W = _f64(W)
     m, n = W.shape
-    p = 1.0 - 0.5 * r
-    upper = min(int(np.floor(n * p)), n - 1)
-    lower = int(np.ceil(n * (1.0 - p)))
+    lower, upper = outlier_cutoff_positions(n, r)
     Ws = np.sort(W, axis=1)
     c_up = Ws[:, upper][:, None]
     c_lo = Ws[:, lower][:, None]

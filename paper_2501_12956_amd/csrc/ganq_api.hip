@@ -224,11 +224,15 @@ ganq_status ganq_outlier_split(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype,
                "col_idx / values / capacity");
   GANQ_REQUIRE(ctx, r >= 0.0 && r < 1.0, "r must be in [0, 1)");
   if (n > 32768) return fail(ctx, GANQ_ERR_UNSUPPORTED, "outlier split sorts a row in LDS: n <= 32768");
-  // sorted positions of the two cut-offs, in double exactly as the definition writes them
-  const double p = 1.0 - 0.5 * r;
-  int64_t upper = (int64_t)floor((double)n * p);
+  // Sorted positions of the two cut-offs: ceil(n (1 - p)) and floor(n p), p = 1 - r/2, taken as
+  // real-number expressions of t = n r / 2 (1 - (1 - r/2) is not r/2 in binary floating point).
+  // A t that is an integer up to rounding is that integer: n = 2000, r = 0.01 cuts at 10 and 1990.
+  double t = (double)n * (0.5 * r);
+  const double tn = nearbyint(t);
+  if (fabs(t - tn) <= 1e-9 * fmax(1.0, fabs(t))) t = tn;
+  int64_t upper = (int64_t)floor((double)n - t);
   if (upper > n - 1) upper = n - 1;
-  const int64_t lower = (int64_t)ceil((double)n * (1.0 - p));
+  const int64_t lower = (int64_t)ceil(t);
   GANQ_REQUIRE(ctx, lower >= 0 && lower <= n - 1, "r too large for this n");
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;

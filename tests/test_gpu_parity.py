@@ -489,7 +489,10 @@ def test_quantize_layer_rank_deficient_activations(ctx, mode):
 
 # ----------------------------------------------------------------------------- Algorithm 2
 @pytest.mark.parametrize("m,n,r,dtype", [(37, 300, 0.05, torch.float32), (8, 1000, 0.005, torch.float16),
-                                         (3, 64, 0.0, torch.float32), (5, 17, 0.3, torch.float16)])
+                                         (3, 64, 0.0, torch.float32), (5, 17, 0.3, torch.float16),
+                                         # n r / 2 an integer that binary rounding of r or of 1 - r/2 could miss
+                                         (4, 2000, 0.01, torch.float32), (3, 1000, 0.1, torch.float16),
+                                         (6, 400, 0.07, torch.float32), (5, 50, 0.28, torch.float32)])
 def test_outlier_split_matches_oracle(ctx, m, n, r, dtype):
     """W = W_sparse + W_dense: no arithmetic on the values, so the split is compared exactly."""
     g = torch.Generator().manual_seed(9)
@@ -513,9 +516,7 @@ def test_outlier_split_matches_oracle(ctx, m, n, r, dtype):
 def _count_masked(W, r):
     """Number of outlier positions of Algorithm 2 (zeros that fall in a tail count too)."""
     n = W.shape[1]
-    p = 1.0 - 0.5 * r
-    upper = min(int(np.floor(n * p)), n - 1)
-    lower = int(np.ceil(n * (1.0 - p)))
+    lower, upper = ref.outlier_cutoff_positions(n, r)
     Ws = np.sort(W, axis=1)
     return int(((W >= Ws[:, upper][:, None]) | (W <= Ws[:, lower][:, None])).sum())
 
@@ -578,7 +579,7 @@ def test_outlier_split_lowers_the_layer_loss(ctx):
 def test_layers_sharing_activations_can_be_stacked(ctx):
     """Layers that see the same input (q/k/v, gate/up) share H and L, and rows are independent
     (Section 3.1): quantising their weights stacked row-wise in one call gives, row for row,
-    what separate calls give."""
+    what separate calls give, and what the oracle gives for the stacked matrix."""
     n, nbits, K = 192, 4, 3
     _, X = make_problem(8, n, 1024, nbits)
     g = torch.Generator().manual_seed(17)
@@ -586,7 +587,8 @@ def test_layers_sharing_activations_can_be_stacked(ctx):
     H = ctx.build_hessian(X.cuda())
     L, info = ctx.cholesky(H)
     assert info == 0
-    Tall, Qall = ctx.quantize_layer(torch.cat(Ws, 0).contiguous(), H, nbits, K, L=L)
+    Wall = torch.cat(Ws, 0).contiguous()
+    Tall, Qall = ctx.quantize_layer(Wall, H, nbits, K, L=L)
     r0 = 0
     for W in Ws:
         T, Q = ctx.quantize_layer(W, H, nbits, K, L=L)
@@ -594,6 +596,26 @@ def test_layers_sharing_activations_can_be_stacked(ctx):
         assert torch.equal(Q, Qall[r0:r0 + mm])
         assert torch.equal(T, Tall[r0:r0 + mm])
         r0 += mm
+    # the stacked call against the oracle: the last sweep's choices are optimal for their float64
+    # targets, T^K is the least-squares refit to Q^K, and the oracle's own K sweeps on the stacked
+    # matrix agree (a near-tie flip may change the earlier columns of single rows)
+    W64 = Wall.cpu().numpy().astype(np.float64)
+    H64 = H.cpu().numpy().astype(np.float64)
+    L64 = L.cpu().numpy().astype(np.float64)
+    Tprev, _ = ctx.quantize_layer(Wall, H, nbits, K - 1, L=L)
+    Qh = Qall.cpu().numpy()
+    _, _, viol = check_S(W64, L64, Tprev.cpu().numpy().astype(np.float64), Qh, "stacked")
+    assert viol == 0
+    Tref, _ = ref.update_T(W64, H64, Qh, nbits)
+    err = np.abs(Tall.cpu().numpy() - Tref).max(axis=1) / np.abs(Tref).max(axis=1)
+    assert err.max() <= 1e-4
+    T0 = ctx.init_codebooks(Wall, nbits).cpu().numpy().astype(np.float64)
+    To, Qo = ref.quantize_layer(W64, H64, T0, nbits, K, L=L64)
+    same = (Qh == Qo).all(axis=1)
+    print("stacked q/k/v: %d of %d rows identical to the oracle's free-running result" % (same.sum(), len(same)))
+    assert same.mean() >= 0.9
+    errT = np.abs(Tall.cpu().numpy()[same] - To[same]).max(axis=1) / np.abs(To[same]).max(axis=1)
+    assert errT.max() <= 1e-4
 
 
 # ----------------------------------------------------------------------------- seeded shape sweep

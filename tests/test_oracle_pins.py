@@ -362,6 +362,41 @@ def test_outlier_split_by_hand():
     assert np.all((Ws == 0) | (Wd == 0))
 
 
+def test_outlier_split_fractional_positions_by_hand():
+    """Algorithm 2 with n r / 2 not an integer: n = 10, r = 0.3, p = 0.85, n p = 8.5,
+    n (1 - p) = 1.5, so upper = floor(8.5) = 8 and lower = ceil(1.5) = 2.  All values are
+    distinct and non-zero, so floor <-> ceil or +-1 on either position changes the mask."""
+    srt = np.array([-9.0, -7.0, -5.0, -3.0, -1.0, 1.0, 3.0, 5.0, 7.0, 9.0])
+    perm = np.array([4, 9, 0, 7, 2, 5, 8, 1, 6, 3])
+    W = srt[perm][None, :]
+    Ws, Wd = ref.outlier_split(W, 0.3)
+    # c_lower = sorted[2] = -5 (entries -9, -7, -5), c_upper = sorted[8] = 7 (entries 7, 9)
+    want = np.where((W <= -5.0) | (W >= 7.0), W, 0.0)
+    assert np.array_equal(Ws, want)
+    assert int((Ws != 0).sum()) == 5
+    assert np.array_equal(Ws + Wd, W)
+    # second row shape: n = 7, r = 0.5 -> n r / 2 = 1.75: lower = 2, upper = floor(5.25) = 5
+    srt = np.array([-6.0, -4.0, -2.0, 0.5, 2.0, 4.0, 6.0])
+    W = srt[[3, 0, 6, 1, 5, 2, 4]][None, :]
+    Ws, _ = ref.outlier_split(W, 0.5)
+    assert np.array_equal(Ws, np.where((W <= -2.0) | (W >= 4.0), W, 0.0))
+
+
+@pytest.mark.parametrize("n,r,lower,upper", [(2000, 0.01, 10, 1990), (1000, 0.1, 50, 950),
+                                              (400, 0.07, 14, 386), (50, 0.28, 7, 43),
+                                              (4096, 0.005, 11, 4085), (10, 0.3, 2, 8),
+                                              (16, 0.0, 0, 15)])
+def test_outlier_cutoff_positions_exact_products(n, r, lower, upper):
+    """ceil(n (1 - p)) and floor(n p) as real-number expressions (Algorithm 2): when n r / 2
+    is an integer the positions are that integer and n minus it, whatever the rounding of r,
+    1 - r/2 or the product in binary floating point (n = 2000, r = 0.01 is 10, not 11)."""
+    assert ref.outlier_cutoff_positions(n, r) == (lower, upper)
+    # the count of outliers in a row of distinct values follows: positions 0..lower and upper..n-1
+    W = np.arange(1, n + 1, dtype=np.float64)[None, ::-1].copy()
+    Ws, _ = ref.outlier_split(W, r)
+    assert int((Ws != 0).sum()) == (lower + 1) + (n - upper)
+
+
 # ------------------------------------------------------------------ Table 1
 def test_storage_model_matches_table1():
     with open(os.path.join(GOLDEN, "table1_storage.txt")) as fh:
