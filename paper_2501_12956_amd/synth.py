@@ -48,9 +48,11 @@ CONFIGS = {
                        "student_t", 5, "gauss", 0.01, 20.0),
     "c4b": LayerConfig("c4b", 4096, 11008, 262144, 4, 10, torch.float16, torch.float16,
                        "student_t", 5, "heavy", 0.005, 30.0),
-    # Llama-3-70B down_proj shape.
+    # Llama-3-70B down_proj shape, 4-bit and 3-bit (same W and X).
     "c5": LayerConfig("c5", 8192, 28672, 131072, 4, 10, torch.float16, torch.float16,
                       "student_t", 4, "heavy", 0.005, 30.0),
+    "c5_3": LayerConfig("c5_3", 8192, 28672, 131072, 3, 10, torch.float16, torch.float16,
+                        "student_t", 4, "heavy", 0.005, 30.0),
 }
 
 _W_OFFSET = 1

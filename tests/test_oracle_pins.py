@@ -324,6 +324,49 @@ def test_alternation_history_and_restartability():
     assert np.allclose(Tc, T, rtol=1e-12, atol=0)
 
 
+@pytest.mark.parametrize("mode,lam", [(ref.PRECOND_DIAGDOM, 0.0), (ref.PRECOND_LAMBDA, 3.0),
+                                      (ref.PRECOND_AUTO, 0.0)])
+def test_preconditioned_run_refits_codebooks_on_the_raw_hessian(mode, lam):
+    """Reading of Algorithm 1 with Appendix A: the factor L of the S-update comes from the
+    preconditioned matrix, while the T-update (Eq. (4)-(7)) and the objective (Eq. (1)) keep the
+    raw H = X X^T.  So T^K must be the least-squares fit to the activations themselves - checked
+    by lstsq on explicit X, not through update_T - and must differ from the fit on L L^T."""
+    rng = np.random.default_rng(31)
+    m, n, p, nbits = 6, 20, 14, 2                       # p < n: H is singular, NONE must fail
+    W = rng.normal(0, 0.02, size=(m, n))
+    X = rng.normal(0, 1, size=(n, p))
+    X[2] *= 8.0
+    H = X @ X.T
+    T0 = ref.init_codebooks(W, nbits)
+    with pytest.raises(ref.NotPositiveDefinite):
+        ref.quantize_layer(W, H, T0, nbits, 2, precond=ref.PRECOND_NONE)
+    T, Q, hist = ref.quantize_layer(W, H, T0, nbits, 3, precond=mode, lam=lam, history=True)
+    Lp, _ = ref.cholesky(H, mode, lam)
+    Hp = Lp @ Lp.T
+    C = 1 << nbits
+    differs = 0
+    for i in range(m):
+        S = np.zeros((C, n))
+        S[Q[i].astype(int), np.arange(n)] = 1.0
+        used = S.sum(axis=1) > 0
+        t_raw = np.zeros(C)
+        t_raw[used] = np.linalg.lstsq((S[used] @ X).T, W[i] @ X, rcond=None)[0]
+        assert np.allclose(T[i], t_raw, rtol=1e-8, atol=1e-12)
+        # the fit against the preconditioned matrix is another vector
+        Xp = Lp                                          # Hp = Lp Lp^T plays X X^T
+        t_pre = np.zeros(C)
+        t_pre[used] = np.linalg.lstsq((S[used] @ Xp).T, W[i] @ Xp, rcond=None)[0]
+        differs += int(not np.allclose(t_pre, t_raw, rtol=1e-3, atol=0))
+    assert differs == m
+    # the recorded objective is the raw one, Eq. (1) evaluated on X itself
+    assert np.isclose(hist[-1], ref.layer_loss_direct(W, X, T, Q), rtol=1e-9)
+    # and the S-update did use the preconditioned factor: every choice of the last sweep is the
+    # argmin for targets built from Lp, not necessarily for targets from another factor
+    Tprev, _ = ref.quantize_layer(W, H, T0, nbits, 2, precond=mode, lam=lam)
+    _, gap, _ = ref.s_update_targets(W, Lp, Tprev, Q)
+    assert np.all(gap == 0)
+
+
 def test_scaling_invariances():
     W, X, H, T0 = small_problem(m=6, n=20, p=90, nbits=2, seed=13)
     T, Q = ref.quantize_layer(W, H, T0, 2, 3)
