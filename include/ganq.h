@@ -209,6 +209,21 @@ ganq_status ganq_outlier_split(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype,
                                int64_t ldw, double r, float* W_dense, int64_t ldd, int64_t* row_ptr,
                                int32_t* col_idx, float* values, int64_t capacity, int64_t* nnz_host);
 
+/* ganq_outlier_split for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments, same kernels, same results, but the per-row scratch (two cut-off values and one
+ * count per row, 12 bytes a row) lives in an array that is part of the library's device image,
+ * 768 KiB per GPU for the life of the process, sized for m <= 65536 rows.  More rows return
+ * GANQ_ERR_UNSUPPORTED.  The call needs no ganq_set_workspace, allocates nothing (no hipMalloc,
+ * hipFree, events or streams) and takes no timing brackets.  All calls on one GPU share that
+ * GPU's array: calls that overlap in time on one GPU (from different contexts or streams) race
+ * and must be serialised by the caller.  Nothing in the array has to survive or be cleared
+ * between calls: every entry a call reads it has written itself.  Synchronises. */
+ganq_status ganq_outlier_split_noalloc(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype, int64_t m,
+                                       int64_t n, int64_t ldw, double r, float* W_dense, int64_t ldd,
+                                       int64_t* row_ptr, int32_t* col_idx, float* values,
+                                       int64_t capacity, int64_t* nnz_host);
+
 /* ---- deployment: stored form and look-up-table product ---------------------- */
 
 /* Stored form of a quantized layer (Table 1): per row the n N-bit codes and a

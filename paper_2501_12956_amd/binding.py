@@ -25,7 +25,7 @@ EXPORTS = ["ganq_create", "ganq_destroy", "ganq_workspace_bytes", "ganq_set_work
            "ganq_status_string", "ganq_last_error", "ganq_build_hessian", "ganq_build_hessian_tokens",
            "ganq_cholesky",
            "ganq_init_codebooks", "ganq_update_S", "ganq_update_T", "ganq_layer_loss",
-           "ganq_quantize_layer", "ganq_outlier_split", "ganq_packed_row_bytes", "ganq_pack_layer",
+           "ganq_quantize_layer", "ganq_outlier_split", "ganq_outlier_split_noalloc", "ganq_packed_row_bytes", "ganq_pack_layer",
            "ganq_lut_gemv", "ganq_profile_enable", "ganq_profile_read"]
 
 KERNEL_CLASSES = ["hessian", "cholesky", "init", "gemm_wh", "update_s", "t_prep", "t_pad", "t_accum",
@@ -95,6 +95,8 @@ def load_library():
     lib.ganq_outlier_split.argtypes = [vp, vp, ci, i64, i64, i64, ctypes.c_double, vp, i64, vp, vp, vp, i64,
                                        ctypes.POINTER(i64)]
     lib.ganq_outlier_split.restype = ci
+    lib.ganq_outlier_split_noalloc.argtypes = lib.ganq_outlier_split.argtypes
+    lib.ganq_outlier_split_noalloc.restype = ci
     lib.ganq_profile_enable.argtypes = [vp, ci]
     lib.ganq_profile_enable.restype = ci
     lib.ganq_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -251,23 +253,26 @@ class Context:
                                              nbits, ctypes.byref(out), _ptr(rows)))
         return (out.value, rows) if want_rows else out.value
 
-    def outlier_split(self, W, r, capacity=None):
+    def outlier_split(self, W, r, capacity=None, noalloc=False):
         """(W_dense fp32, row_ptr int64, col_idx int32, values fp32) of Algorithm 2; the CSR
-        arrays are trimmed to the number of outliers."""
+        arrays are trimmed to the number of outliers.  noalloc=True takes the entry point whose
+        scratch is part of the library image (no workspace is reserved or used)."""
         m, n = W.shape
         dev = W.device
         Wd = torch.empty(m, n, dtype=torch.float32, device=dev)
         row_ptr = torch.empty(m + 1, dtype=torch.int64, device=dev)
-        self.reserve(m, n, 0, 4)
+        fn = self.lib.ganq_outlier_split_noalloc if noalloc else self.lib.ganq_outlier_split
+        if not noalloc:
+            self.reserve(m, n, 0, 4)
         if capacity is None:
             capacity = m * (2 * (int(n * r * 0.5) + 2) + 8)
         nnz = ctypes.c_int64(0)
         for _ in range(2):
             col = torch.empty(max(capacity, 1), dtype=torch.int32, device=dev)
             val = torch.empty(max(capacity, 1), dtype=torch.float32, device=dev)
-            st = self.lib.ganq_outlier_split(self.handle, _ptr(W), _dtype_code(W), m, n, _rowmajor(W, "W"),
-                                             float(r), _ptr(Wd), n, _ptr(row_ptr), _ptr(col), _ptr(val),
-                                             capacity, ctypes.byref(nnz))
+            st = fn(self.handle, _ptr(W), _dtype_code(W), m, n, _rowmajor(W, "W"),
+                    float(r), _ptr(Wd), n, _ptr(row_ptr), _ptr(col), _ptr(val),
+                    capacity, ctypes.byref(nnz))
             if st == GANQ_ERR_INVALID_ARG and nnz.value > capacity:
                 capacity = nnz.value          # ties at a cut-off: size the arrays exactly and repeat
                 continue

@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "ganq_internal.h"
@@ -153,6 +154,99 @@ ganq_status run_cholesky(ganq_ctx* ctx, Arena& ar, const float* H, int64_t n, in
   return GANQ_OK;
 }
 
+// ---- scratch of the allocation-free outlier split ----
+// Per-row cut-off pairs and outlier counts of at most kStaticOutlierRows rows, laid out exactly as
+// launch_outlier_split lays out a workspace of that many rows.  Every device the library runs on
+// holds its own copy of this array at its own address until the process ends; the name below is
+// only a host-side handle, the device address comes from hipGetSymbolAddress once per device.
+constexpr int64_t kStaticOutlierRows = 65536;
+constexpr size_t kStaticOutlierBytes = 2 * sizeof(float) * kStaticOutlierRows + sizeof(int32_t) * kStaticOutlierRows;
+static __device__ __align__(256) unsigned char g_outlier_scratch[kStaticOutlierBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_outlier_mu;
+void* g_outlier_ptr[kMaxDevices] = {nullptr};
+
+// Device address of this device's copy of the array; the device must be current.
+hipError_t static_outlier_scratch(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_outlier_mu);
+  if (g_outlier_ptr[device] == nullptr) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_outlier_scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    g_outlier_ptr[device] = p;
+  }
+  *out = g_outlier_ptr[device];
+  return hipSuccess;
+}
+
+// Both outlier-split entry points; they differ only in where the per-row scratch lives.
+ganq_status outlier_split_impl(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype, int64_t m, int64_t n,
+                               int64_t ldw, double r, float* W_dense, int64_t ldd, int64_t* row_ptr,
+                               int32_t* col_idx, float* values, int64_t capacity, int64_t* nnz_host,
+                               bool static_scratch) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  if (nnz_host != nullptr) *nnz_host = 0;
+  GANQ_REQUIRE(ctx, dtype_ok(w_dtype), "w_dtype");
+  GANQ_REQUIRE(ctx, m > 0 && n > 0, "m and n must be positive");
+  GANQ_REQUIRE(ctx, W != nullptr && ldw >= n, "W / ldw");
+  GANQ_REQUIRE(ctx, W_dense != nullptr && ldd >= n, "W_dense / ldd");
+  GANQ_REQUIRE(ctx, row_ptr != nullptr && nnz_host != nullptr, "row_ptr / nnz_host");
+  GANQ_REQUIRE(ctx, capacity >= 0 && (capacity == 0 || (col_idx != nullptr && values != nullptr)),
+               "col_idx / values / capacity");
+  GANQ_REQUIRE(ctx, r >= 0.0 && r < 1.0, "r must be in [0, 1)");
+  if (n > 32768) return fail(ctx, GANQ_ERR_UNSUPPORTED, "outlier split sorts a row in LDS: n <= 32768");
+  if (static_scratch && (m > kStaticOutlierRows || outlier_scratch_bytes(m) > kStaticOutlierBytes))
+    return fail(ctx, GANQ_ERR_UNSUPPORTED,
+                "ganq_outlier_split_noalloc holds scratch for at most 65536 rows: split the layer by rows "
+                "or use ganq_outlier_split with a workspace");
+  // Sorted positions of the two cut-offs: ceil(n (1 - p)) and floor(n p), p = 1 - r/2, taken as
+  // real-number expressions of t = n r / 2 (1 - (1 - r/2) is not r/2 in binary floating point).
+  // A t that is an integer up to rounding is that integer: n = 2000, r = 0.01 cuts at 10 and 1990.
+  double t = (double)n * (0.5 * r);
+  const double tn = nearbyint(t);
+  if (fabs(t - tn) <= 1e-9 * fmax(1.0, fabs(t))) t = tn;
+  int64_t upper = (int64_t)floor((double)n - t);
+  if (upper > n - 1) upper = n - 1;
+  const int64_t lower = (int64_t)ceil(t);
+  GANQ_REQUIRE(ctx, lower >= 0 && lower <= n - 1, "r too large for this n");
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  hipStream_t s = ctx->stream;
+  void* scratch = nullptr;
+  if (static_scratch) {
+    // every entry the kernels read is written earlier in the same call (cut-offs and counts of rows
+    // 0..m-1), so nothing left by a previous call has to be cleared
+    GANQ_HIP(ctx, static_outlier_scratch(ctx->device, &scratch));
+  } else {
+    Arena ar(ctx->ws, ctx->ws_bytes);
+    scratch = ar.take(outlier_scratch_bytes(m));
+    if (scratch == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the outlier split");
+  }
+  if (static_scratch) {
+    // no event brackets here: they may create HIP events
+    GANQ_HIP(ctx, launch_outlier_split(s, W, w_dtype == GANQ_F16, m, n, ldw, (int)lower, (int)upper, W_dense,
+                                       ldd, row_ptr, col_idx, values, capacity, scratch));
+  } else {
+    ProfScope prof(ctx, GANQ_K_OUTLIER);
+    GANQ_HIP(ctx, launch_outlier_split(s, W, w_dtype == GANQ_F16, m, n, ldw, (int)lower, (int)upper, W_dense,
+                                       ldd, row_ptr, col_idx, values, capacity, scratch));
+  }
+  int64_t nnz = 0;
+  GANQ_HIP(ctx, hipMemcpyAsync(&nnz, row_ptr + m, sizeof(int64_t), hipMemcpyDeviceToHost, s));
+  GANQ_HIP(ctx, hipStreamSynchronize(s));
+  *nnz_host = nnz;
+  if (nnz > capacity) {
+    char buf[128];
+    snprintf(buf, sizeof buf, "%lld outliers do not fit a capacity of %lld", (long long)nnz,
+             (long long)capacity);
+    return fail(ctx, GANQ_ERR_INVALID_ARG, buf);
+  }
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -213,50 +307,16 @@ ganq_status ganq_set_workspace(ganq_ctx* ctx, void* dev_ptr, size_t bytes) {
 ganq_status ganq_outlier_split(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype, int64_t m, int64_t n,
                                int64_t ldw, double r, float* W_dense, int64_t ldd, int64_t* row_ptr,
                                int32_t* col_idx, float* values, int64_t capacity, int64_t* nnz_host) {
-  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
-  if (nnz_host != nullptr) *nnz_host = 0;
-  GANQ_REQUIRE(ctx, dtype_ok(w_dtype), "w_dtype");
-  GANQ_REQUIRE(ctx, m > 0 && n > 0, "m and n must be positive");
-  GANQ_REQUIRE(ctx, W != nullptr && ldw >= n, "W / ldw");
-  GANQ_REQUIRE(ctx, W_dense != nullptr && ldd >= n, "W_dense / ldd");
-  GANQ_REQUIRE(ctx, row_ptr != nullptr && nnz_host != nullptr, "row_ptr / nnz_host");
-  GANQ_REQUIRE(ctx, capacity >= 0 && (capacity == 0 || (col_idx != nullptr && values != nullptr)),
-               "col_idx / values / capacity");
-  GANQ_REQUIRE(ctx, r >= 0.0 && r < 1.0, "r must be in [0, 1)");
-  if (n > 32768) return fail(ctx, GANQ_ERR_UNSUPPORTED, "outlier split sorts a row in LDS: n <= 32768");
-  // Sorted positions of the two cut-offs: ceil(n (1 - p)) and floor(n p), p = 1 - r/2, taken as
-  // real-number expressions of t = n r / 2 (1 - (1 - r/2) is not r/2 in binary floating point).
-  // A t that is an integer up to rounding is that integer: n = 2000, r = 0.01 cuts at 10 and 1990.
-  double t = (double)n * (0.5 * r);
-  const double tn = nearbyint(t);
-  if (fabs(t - tn) <= 1e-9 * fmax(1.0, fabs(t))) t = tn;
-  int64_t upper = (int64_t)floor((double)n - t);
-  if (upper > n - 1) upper = n - 1;
-  const int64_t lower = (int64_t)ceil(t);
-  GANQ_REQUIRE(ctx, lower >= 0 && lower <= n - 1, "r too large for this n");
-  ganq_status st = bind_device(ctx);
-  if (st != GANQ_OK) return st;
-  hipStream_t s = ctx->stream;
-  Arena ar(ctx->ws, ctx->ws_bytes);
-  void* scratch = ar.take(outlier_scratch_bytes(m));
-  if (scratch == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the outlier split");
-  {
-    ProfScope prof(ctx, GANQ_K_OUTLIER);
-    GANQ_HIP(ctx, launch_outlier_split(s, W, w_dtype == GANQ_F16, m, n, ldw, (int)lower, (int)upper, W_dense,
-                                       ldd, row_ptr, col_idx, values, capacity, scratch));
-  }
-  int64_t nnz = 0;
-  GANQ_HIP(ctx, hipMemcpyAsync(&nnz, row_ptr + m, sizeof(int64_t), hipMemcpyDeviceToHost, s));
-  GANQ_HIP(ctx, hipStreamSynchronize(s));
-  *nnz_host = nnz;
-  if (nnz > capacity) {
-    char buf[128];
-    snprintf(buf, sizeof buf, "%lld outliers do not fit a capacity of %lld", (long long)nnz,
-             (long long)capacity);
-    return fail(ctx, GANQ_ERR_INVALID_ARG, buf);
-  }
-  ctx->last_error.clear();
-  return GANQ_OK;
+  return outlier_split_impl(ctx, W, w_dtype, m, n, ldw, r, W_dense, ldd, row_ptr, col_idx, values, capacity,
+                            nnz_host, false);
+}
+
+ganq_status ganq_outlier_split_noalloc(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype, int64_t m,
+                                       int64_t n, int64_t ldw, double r, float* W_dense, int64_t ldd,
+                                       int64_t* row_ptr, int32_t* col_idx, float* values,
+                                       int64_t capacity, int64_t* nnz_host) {
+  return outlier_split_impl(ctx, W, w_dtype, m, n, ldw, r, W_dense, ldd, row_ptr, col_idx, values, capacity,
+                            nnz_host, true);
 }
 
 int64_t ganq_packed_row_bytes(int64_t n, int nbits) {
