@@ -36,23 +36,50 @@ PEAK_F32_MFMA_TFLOPS = 157.3
 # plain fp32 vector additions: 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2.4 GHz = 78.6e12 adds/s,
 # i.e. half of the 157.3 TFLOP/s vector FMA figure (an add is one flop, an FMA two)
 PEAK_F32_ADD_TOPS = 78.6
+PEAK_I8_TOPS = 5000.0
 
 
-# HBM bytes per launch on config c3 (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc, each scaled by the
-# reading of a plain 1 GiB copy: x2.000 and x1.000); copied from profiles/bench_c3_hbm_traffic.txt,
-# which gives the commands.  Other configs report null.
-TRAFFIC_C3_BYTES = {
-    "hessian": (12779.74 + 580.15) * 2 ** 20,     # product kernel + reduction
-    "update_s": 1949.42 * 2 ** 20,
-    "t_accum": 1127.82 * 2 ** 20,
-    "t_solve": 145.09 * 2 ** 20,
-    "t_pad": 64.02 * 2 ** 20,
-    "gemm_wh": (930.41 + 2 * 64.10 + 2 * 128.01) * 2 ** 20,     # piece product + 2 x (absmax, split)
-    "loss": (930.41 + 2 * 64.10 + 2 * 128.01 + 146.03 + 128.15) * 2 ** 20,
-    "init": (96.03 + 64.34) * 2 ** 20,
-    "cholesky": (128.34 + 15 * 34.91 + 64 * 2.27) * 2 ** 20,
-    "t_prep": (0.54 + 32.75 + 48.81) * 2 ** 20,   # diagonal, row scales, digits
+# Kernels behind each timed class: (main kernel, [other kernels launched inside the class's bracket]).
+# HBM traffic per class launch = sum over these kernels of (MiB per launch x launches in one step) of the
+# table in profiles/<file> (FETCH_SIZE and WRITE_SIZE of rocprofv3 --pmc, already scaled there by the
+# reading of a plain copy), divided by the main kernel's launches.
+CLASS_KERNELS = {
+    "hessian": ("hessian_f16_kernel", ["reduce_mirror_kernel"]),
+    "cholesky": ("copy_lower_kernel", ["chol_panel_kernel", "gemm_f32_kernel", "syrk_f32_kernel", "fill_i32_kernel"]),
+    "init": ("init_codebooks_kernel", ["convert_f16_f32_kernel"]),
+    "update_s": ("update_S_kernel", ["rdiag_kernel"]),
+    "t_prep": ("t_split_kernel", ["t_diag_kernel", "t_rowscale_kernel"]),
+    "t_pad": ("pad_q_kernel", []),
+    "t_accum": ("t_accum_kernel", []),
+    "t_solve": ("t_solve_kernel", []),
 }
+TRAFFIC_FILES = {"c3": "bench_c3_hbm_traffic.txt"}
+
+
+def load_traffic(config_name):
+    """{class: HBM bytes per class launch} from the committed rocprofv3 summary of this workload, or {}."""
+    fn = TRAFFIC_FILES.get(config_name)
+    path = os.path.join(ROOT, "profiles", fn) if fn else None
+    if not path or not os.path.exists(path):
+        return {}
+    rows = {}
+    for ln in open(path):
+        f = ln.split()
+        if len(f) == 5 and not ln.startswith("#") and f[1].isdigit():
+            rows[f[0].split("<")[0]] = (int(f[1]), float(f[4]) * 2 ** 20)        # launches, bytes per launch
+    out = {}
+    for cls, (main, others) in CLASS_KERNELS.items():
+        if main not in rows:
+            continue
+        total = sum(rows[k][0] * rows[k][1] for k in [main] + others if k in rows)
+        out[cls] = total / rows[main][0]
+    # the two split-fp16 products (G = W H inside the solver, F = E H in the loss) share their kernels
+    if "gemm_split_kernel" in rows:
+        g = rows["gemm_split_kernel"][1]
+        aux = 2 * rows.get("absmax_kernel", (0, 0.0))[1] + 2 * rows.get("split_kernel", (0, 0.0))[1]
+        out["gemm_wh"] = g + aux
+        out["loss"] = g + aux + rows.get("residual_kernel", (0, 0.0))[1] + rows.get("rowdot_kernel", (0, 0.0))[1]
+    return out
 
 
 def kernel_work(cls, m, n, p, nbits, iters):
@@ -66,7 +93,7 @@ def kernel_work(cls, m, n, p, nbits, iters):
         return "mfma", 2.0 * m * n * n, "TFLOP/s", PEAK_F16_TFLOPS
     if cls == "update_s":
         return "mfma", float(m) * n * n, "TFLOP/s", PEAK_F32_MFMA_TFLOPS      # triangular: m n^2 / 2 MACs
-    if cls == "t_accum":
+    if cls in ("t_accum", "t_delta"):
         return "alu", 0.5 * m * n * n, "TFLOP/s", PEAK_F32_ADD_TOPS           # m n^2 / 2 additions
     if cls == "loss":
         return "mfma", 2.0 * m * n * n, "TFLOP/s", PEAK_F16_TFLOPS
@@ -219,6 +246,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peak-probe", action="store_true",
+                    help="skip the on-box peak measurement (fractions of measured peaks are then null)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region: under "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE its reading gives the scale of the counter")
@@ -264,6 +293,9 @@ def main():
         calib[1].copy_(calib[0])                                            # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del calib
+    peaks = {}
+    if not args.no_peak_probe:
+        peaks = ctx.measure_peaks()         # bare MFMA loops and a device copy, about 0.1 s
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -277,6 +309,20 @@ def main():
     ctx.profile_enable(False)
     ms_per_step = 1e3 * elapsed / args.steps
 
+    traffic = load_traffic(cfg.name)
+    # peak the same silicon sustains on a bare loop, by the unit and arithmetic of each class
+    def measured_peak(cls, unit, bound):
+        if not peaks:
+            return None
+        if unit == "GB/s":
+            return peaks["copy_gbs"]
+        if cls in ("hessian", "gemm_wh", "loss"):
+            return peaks["f16_mfma_tflops"]
+        if cls in ("t_accum", "t_delta"):
+            # additions that run as int8 one-hot products: 2 C digits operations issued per addition
+            return peaks["i8_mfma_tops"] / (2.0 * (1 << cfg.nbits) * 2)
+        return peaks["f32_mfma_tflops"]
+
     kernels = {}
     for cls, (ms, cnt) in prof.items():
         if cnt == 0:
@@ -284,21 +330,41 @@ def main():
         bound, work, unit, peak = kernel_work(cls, m, n, p, cfg.nbits, cfg.iters)
         avg_ms = ms / cnt
         rate = work / (avg_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9) if avg_ms > 0 else 0.0
+        mp = measured_peak(cls, unit, bound)
         kernels[cls] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps,
                         "avg_ms": avg_ms, "bound": bound, "achieved": rate, "peak": peak, "unit": unit,
                         "frac": rate / peak,
-                        "traffic": TRAFFIC_C3_BYTES.get(cls) if cfg.name == "c3" else None}
+                        "measured_peak": mp, "frac_of_measured_peak": (rate / mp) if mp else None,
+                        "traffic": traffic.get(cls)}
+        if cls == "t_accum":
+            # what the matrix cores execute for those additions: one-hot int8 products, C columns per
+            # row and two base-256 digits per entry (three or four on strongly correlated H)
+            issued = 2.0 * (1 << cfg.nbits) * 2 * work
+            kernels[cls]["issued"] = {"int8_ops_per_launch": issued,
+                                      "rate_tops": issued / (avg_ms * 1e-3) / 1e12, "peak_tops": PEAK_I8_TOPS,
+                                      "frac": issued / (avg_ms * 1e-3) / 1e12 / PEAK_I8_TOPS,
+                                      "note": "two-digit tiles assumed; bound \"alu\" above counts the additions"}
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     kd = kernels[dominant]
     roofline = {"kernel": dominant, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
                 "unit": kd["unit"], "frac": kd["frac"], "traffic": kd["traffic"],
-                "avg_launch_ms": kd["avg_ms"]}
+                "avg_launch_ms": kd["avg_ms"], "measured_peak": kd["measured_peak"],
+                "frac_of_measured_peak": kd["frac_of_measured_peak"]}
 
+    if cfg.m == 4096 and cfg.n == 4096 and cfg.nbits == 4 and cfg.iters == 10:
+        metric = "sec per 4096x4096 layer (4-bit, 10 iters) on 1 GPU; % MFMA/HBM roofline"
+    else:
+        metric = ("sec per %dx%d layer (%d-bit, %d iters) on 1 GPU; %% MFMA/HBM roofline"
+                  % (m, n, cfg.nbits, cfg.iters))
     out = {
-        "metric": "sec per 4096x4096 layer (4-bit, 10 iters) on 1 GPU; % MFMA/HBM roofline",
+        "metric": metric,
         "value": ms_per_step / 1e3, "unit": "s/layer", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None,
+        # storage and the S-update are fp32; what else runs is listed, not hidden behind "f32"
+        "dtype": "f32 (H build: f16 x f16 -> f32; T-update sums: exact int32 over base-256 int8 digits of H; "
+                 "G = W H and the loss product: two-piece f16 splits, f32 accumulate; per-row solve: f64)",
+        "data": "synthetic",
         "config": {"workload": "%s: W %dx%d %s, X %dx%d %s, N=%d bits, %d alternations; step = H build + "
                                "Cholesky + codebook init + alternations + loss"
                                % (cfg.name, m, n, str(cfg.w_dtype).replace("torch.", ""), n, p,
@@ -306,6 +372,7 @@ def main():
         "final_loss": state["loss"],
         "roofline": roofline,
         "kernels": kernels,
+        "measured_peaks": peaks or None,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, X, W)

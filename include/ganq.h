@@ -281,6 +281,15 @@ ganq_status ganq_profile_enable(ganq_ctx* ctx, int on);
  * of bracketed launches per class (arrays of GANQ_K_COUNT, host memory). */
 ganq_status ganq_profile_read(ganq_ctx* ctx, double* ms_host, int64_t* launches_host);
 
+/* Rates this GPU sustains on bare loops, for roofline fractions against measured rather than
+ * published peaks: peaks_host[0] = fp16 matrix-core TFLOP/s (v_mfma_f32_32x32x16_f16),
+ * [1] = fp32 matrix-core TFLOP/s (v_mfma_f32_32x32x2_f32), [2] = int8 matrix-core TOP/s
+ * (v_mfma_i32_32x32x32_i8), each from a register-resident loop with four independent
+ * accumulators per wavefront and two wavefronts per SIMD; [3] = GB/s (read + write) of a plain
+ * device copy of half the workspace (at most 1 GiB).  Best of three timed launches each, HIP
+ * events on the context's stream.  Needs a workspace of at least 2 MiB.  Synchronises. */
+ganq_status ganq_measure_peaks(ganq_ctx* ctx, double* peaks_host /* 4 */);
+
 #ifdef __cplusplus
 }
 #endif

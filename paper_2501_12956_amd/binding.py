@@ -26,7 +26,7 @@ EXPORTS = ["ganq_create", "ganq_destroy", "ganq_workspace_bytes", "ganq_set_work
            "ganq_cholesky",
            "ganq_init_codebooks", "ganq_update_S", "ganq_update_T", "ganq_layer_loss",
            "ganq_quantize_layer", "ganq_outlier_split", "ganq_outlier_split_noalloc", "ganq_packed_row_bytes", "ganq_pack_layer",
-           "ganq_lut_gemv", "ganq_profile_enable", "ganq_profile_read"]
+           "ganq_lut_gemv", "ganq_profile_enable", "ganq_profile_read", "ganq_measure_peaks"]
 
 KERNEL_CLASSES = ["hessian", "cholesky", "init", "gemm_wh", "update_s", "t_prep", "t_pad", "t_accum",
                   "t_solve", "loss", "outlier", "pack", "lut_gemv"]
@@ -101,6 +101,8 @@ def load_library():
     lib.ganq_profile_enable.restype = ci
     lib.ganq_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     lib.ganq_profile_read.restype = ci
+    lib.ganq_measure_peaks.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
+    lib.ganq_measure_peaks.restype = ci
     _lib = lib
     return lib
 
@@ -179,6 +181,15 @@ class Context:
         cnt = (ctypes.c_int64 * k)()
         self._check(self.lib.ganq_profile_read(self.handle, ms, cnt))
         return {name: (ms[i], cnt[i]) for i, name in enumerate(KERNEL_CLASSES)}
+
+    def measure_peaks(self):
+        """Sustained on-box rates: {"f16_mfma_tflops", "f32_mfma_tflops", "i8_mfma_tops", "copy_gbs"}."""
+        if self._ws is None:
+            self._ws = torch.empty(2 << 30, dtype=torch.uint8, device=self.device)
+            self._check(self.lib.ganq_set_workspace(self.handle, _ptr(self._ws), self._ws.numel()))
+        out = (ctypes.c_double * 4)()
+        self._check(self.lib.ganq_measure_peaks(self.handle, out))
+        return {"f16_mfma_tflops": out[0], "f32_mfma_tflops": out[1], "i8_mfma_tops": out[2], "copy_gbs": out[3]}
 
     # ---- the seven calls -------------------------------------------------
     def build_hessian(self, X, H=None, accumulate=False):

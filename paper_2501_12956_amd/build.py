@@ -21,7 +21,7 @@ LIB = os.path.join(PKG, "libganq.so")
 
 SOURCES = ["ganq_api.hip", "gemm_f32.hip", "hessian.hip", "cholesky.hip", "init_codebooks.hip",
            "update_s.hip", "update_t.hip", "loss.hip", "outlier_split.hip", "gemm_split.hip",
-           "lut_gemv.hip"]
+           "lut_gemv.hip", "peaks.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed fp32 VALU forms are kept off for every kernel in this library

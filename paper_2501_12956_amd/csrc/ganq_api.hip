@@ -399,6 +399,47 @@ ganq_status ganq_profile_read(ganq_ctx* ctx, double* ms_host, int64_t* launches_
   return GANQ_OK;
 }
 
+ganq_status ganq_measure_peaks(ganq_ctx* ctx, double* peaks_host) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  GANQ_REQUIRE(ctx, peaks_host != nullptr, "peaks_host");
+  for (int k = 0; k < 4; ++k) peaks_host[k] = 0.0;
+  if (ctx->ws == nullptr || ctx->ws_bytes < ((size_t)2 << 20))
+    return fail(ctx, GANQ_ERR_WORKSPACE, "ganq_measure_peaks needs a workspace of at least 2 MiB");
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  hipStream_t s = ctx->stream;
+  size_t half = ctx->ws_bytes / 2;
+  if (half > ((size_t)1 << 30)) half = (size_t)1 << 30;
+  half &= ~(size_t)255;
+  hipEvent_t a = nullptr, b = nullptr;
+  GANQ_HIP(ctx, hipEventCreate(&a));
+  hipError_t e = hipEventCreate(&b);
+  if (e != hipSuccess) {
+    hipEventDestroy(a);
+    return hip_fail(ctx, e, "hipEventCreate");
+  }
+  for (int which = 0; which < 4 && e == hipSuccess; ++which) {
+    double best = 0.0;
+    for (int rep = 0; rep < 4 && e == hipSuccess; ++rep) {       // the first launch warms up
+      double ops = 0.0;
+      float ms = 0.f;
+      if ((e = hipEventRecord(a, s)) != hipSuccess) break;
+      if ((e = launch_peak_probe(s, which, ctx->ws, half, &ops)) != hipSuccess) break;
+      if ((e = hipEventRecord(b, s)) != hipSuccess) break;
+      if ((e = hipEventSynchronize(b)) != hipSuccess) break;
+      if ((e = hipEventElapsedTime(&ms, a, b)) != hipSuccess) break;
+      const double rate = (which < 3) ? ops / (ms * 1e-3) / 1e12 : ops / (ms * 1e-3) / 1e9;
+      if (rep > 0 && rate > best) best = rate;
+    }
+    peaks_host[which] = best;
+  }
+  hipEventDestroy(a);
+  hipEventDestroy(b);
+  if (e != hipSuccess) return hip_fail(ctx, e, "peak probe");
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
 const char* ganq_status_string(ganq_status s) {
   switch (s) {
     case GANQ_OK: return "ok";
@@ -472,6 +513,10 @@ ganq_status ganq_build_hessian_tokens(ganq_ctx* ctx, const void* Xt, ganq_dtype 
     const int64_t fit = (int64_t)((ctx->ws_bytes - part_bytes - 4 * kAlign) / ((size_t)n * eb)) / 2048 * 2048;
     if (fit > chunk) chunk = fit < p8 ? fit : p8;
   }
+  // the fp16 product addresses a 256-row block of its operand with 32-bit byte offsets: the
+  // leading dimension of the transposed chunk (= its token count) must stay below 2^22
+  constexpr int64_t kMaxChunkF16 = ((int64_t)1 << 22) - 2048;
+  if (x_dtype == GANQ_F16 && chunk > kMaxChunkF16) chunk = kMaxChunkF16;
   Arena ar(ctx->ws, ctx->ws_bytes);
   void* Xn = ar.take((size_t)n * chunk * eb);
   float* part = (float*)ar.take(part_bytes);
@@ -717,7 +762,7 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
         ProfScope prof(ctx, GANQ_K_GEMM_WH, pre);
         if ((e = launch_gemm_split(pre, m, n, n, Wf, ldwf, H, ldh, G, n, gs, 0)) != hipSuccess) return e;
       }
-      // the fp16 split of H is made once per layer
+      // the integer digits of H are made once per layer
       ProfScope prof(ctx, GANQ_K_T_PREP, pre);
       if ((e = launch_t_prepare(pre, H, m, n, ldh, nbits, t_scratch)) != hipSuccess) return e;
     }

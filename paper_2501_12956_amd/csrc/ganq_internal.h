@@ -137,6 +137,8 @@ hipError_t launch_lut_gemv(hipStream_t s, const uint8_t* packed, int64_t ldp, co
                            int64_t m, int64_t n, const _Float16* x, float* y, const int64_t* row_ptr,
                            const int32_t* col_idx, const float* values);
 
+hipError_t launch_peak_probe(hipStream_t s, int which, void* buf, size_t bytes, double* ops);
+
 // ---- kernel launchers (all enqueue on `s`, return the HIP error of the launch) ----
 
 // C = alpha * A * op(B) + beta * C, fp32 on the matrix cores.  A is M x K
@@ -165,7 +167,7 @@ hipError_t launch_update_S(hipStream_t s, const float* W, int64_t m, int64_t n, 
                            const float* L, int64_t ldl, const float* T, int nbits, uint8_t* Q,
                            int64_t ldq, float* E, int64_t lde, void* scratch);
 
-// T-update in four steps on one scratch region: fp16 split of H (once per layer), padded
+// T-update in four steps on one scratch region: integer digits of H (once per layer), padded
 // copy of Q, the one-hot GEMM with fold epilogue, and the per-row assembly + solve
 // (G = W * H is an input, computed once per layer).
 hipError_t launch_t_prepare(hipStream_t s, const float* H, int64_t m, int64_t n, int64_t ldh,

@@ -287,6 +287,7 @@ size_t hessian_scratch_bytes(int64_t n, int64_t p) {
 // Requires p % 8 == 0, ldx % 8 == 0, ldx < 2^22 and a 16-byte aligned X (checked by the caller).
 hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64_t p, int64_t ldx,
                               float* H, int64_t ldh, int accumulate, float* partials) {
+  if (ldx >= ((int64_t)1 << 22) || (p % 8) != 0 || (ldx % 8) != 0) return hipErrorInvalidValue;
   const int split = hessian_split(n, p);
   int64_t chunk = ceil_div(ceil_div(p, split), HK) * HK;
   const int64_t nt = ceil_div(n, HT);

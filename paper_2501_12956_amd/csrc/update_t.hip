@@ -40,9 +40,12 @@ namespace ganq {
 namespace {
 
 constexpr int TM = 128;    // rows j of H per tile
-constexpr int TN = 512;    // (row i, code b) pairs per workgroup
+// Four wavefronts per workgroup, each 128 x 64 of the tile, and two workgroups per compute unit
+// (72 KB of LDS each): the two wavefronts that share a SIMD then belong to different workgroups
+// and are not held to the same barrier, so one's staging work runs under the other's MFMAs.
+constexpr int TNW = 4;
+constexpr int TN = 64 * TNW;    // (row i, code b) pairs per workgroup
 constexpr int TK = 64;     // k per stage
-constexpr int TNW = 8;     // wavefronts per workgroup, each 128 x 64 of the tile
 constexpr int TP = 4;      // most base-256 digits per entry
 constexpr int EMAX = 6;    // largest column exponent (the one-hot entry 2^e is an int8)
 constexpr float V2MAX = 32512.f;     // largest |v| with two digits:  127 * 256 + 127 - 127
@@ -281,7 +284,7 @@ template <int V> struct IntC { static constexpr int value = V; };
 // l % C, else 0.  With C < 16 a 16-column group spans several rows i and only the diagonal
 // C x C blocks of the 16 x 16 result are meaningful; the others are never stored.
 template <int NBITS>
-__global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const int8_t* __restrict__ Hs,
+__global__ __launch_bounds__(64 * TNW, 2) void t_accum_kernel(const int8_t* __restrict__ Hs,
                                                            int64_t npad, const uint8_t* __restrict__ Qp,
                                                            const uint16_t* __restrict__ Qo,
                                                            const uint8_t* __restrict__ Cs,
@@ -344,10 +347,14 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const int8_t* __restr
     }
   }
 
-  // direct load of the A tile: one instruction covers 16 rows x 64 bytes, one per wavefront
+  // direct load of the A tile: one instruction covers 16 rows x 64 bytes; TM / 16 of them are
+  // dealt to the wavefronts
+  constexpr int ALD = (TM / 16) / TNW;
   const int dr = lane >> 2;
   const int dc = (lane & 3) ^ ((dr >> 1) & 3);
-  const uint32_t voff = (uint32_t)((int64_t)(wave * 16 + dr) * npad + dc * 16);
+  uint32_t voff[ALD];
+#pragma unroll
+  for (int a = 0; a < ALD; ++a) voff[a] = (uint32_t)((int64_t)((wave + TNW * a) * 16 + dr) * npad + dc * 16);
 
   const int rswz = (l32 >> 1) & 3;
   // per-lane LDS byte offsets of the fragments inside a stage
@@ -439,7 +446,9 @@ __global__ __launch_bounds__(64 * TNW) void t_accum_kernel(const int8_t* __restr
         rsA[3] = 0x00020000;
       }
       auto issue = [&](int k, int st) {
-        load16_to_lds(rsA, lds0 + st * T_STAGEB + wave * 1024, voff, (uint32_t)k * (uint32_t)TK);
+#pragma unroll
+        for (int a = 0; a < ALD; ++a)
+          load16_to_lds(rsA, lds0 + st * T_STAGEB + (wave + TNW * a) * 1024, voff[a], (uint32_t)k * (uint32_t)TK);
       };
       if (dg > 0 && shared_acc) {
         // next digit: everything so far moves up by one digit

@@ -138,3 +138,26 @@ def test_full_solver_on_sampled_rows(layer):
                                                           float((QKs == Qo).all(axis=1).mean())))
     assert hist[-1] < hist[0]
     assert abs(lref - lo) <= 1e-2 * lo
+
+
+def test_seven_call_alternation_equals_the_driver_and_flip_fractions(layer):
+    """Algorithm 1 driven from outside through ganq_init_codebooks / ganq_update_S / ganq_update_T
+    gives bit for bit what ganq_quantize_layer gives, and the fraction of indices that change from
+    one sweep to the next is reported (it bounds what an incremental T-update could save)."""
+    cfg, ctx, W, H, L = (layer[k] for k in ("cfg", "ctx", "W", "H", "L"))
+    Wf = W.float()
+    nbits, K = cfg.nbits, cfg.iters
+    T = ctx.init_codebooks(W, nbits)
+    Qprev = None
+    flips = []
+    for k in range(K):
+        Q = ctx.update_S(Wf, L, T, nbits)
+        if Qprev is not None:
+            flips.append(float((Q != Qprev).float().mean()))
+        Qprev = Q
+        T = ctx.update_T(Wf, H, Q, T, nbits)
+    TK, QK = ctx.quantize_layer(W, H, nbits, K, L=L)
+    assert torch.equal(QK, Qprev) and torch.equal(TK, T)
+    print("c3 fraction of indices changed between consecutive sweeps (2..%d): %s"
+          % (K, " ".join("%.4f" % f for f in flips)))
+    assert all(f < 0.5 for f in flips)

@@ -104,7 +104,10 @@ def test_hessian_fp32_and_strided(ctx):
 
 
 @pytest.mark.parametrize("n,p,dtype", [(300, 1093, torch.float16), (130, 5, torch.float16),
-                                       (200, 515, torch.float32)])
+                                       (200, 515, torch.float32),
+                                       # more than 2^22 tokens with room to transpose them all at once: the
+                                       # fp16 product takes chunks whose leading dimension stays below 2^22
+                                       (8, (1 << 22) + 4104, torch.float16)])
 def test_hessian_token_major(ctx, n, p, dtype):
     """Activations stored tokens x features (how calibration batches arrive): H = Xt^T Xt, any
     token count, chunks accumulated; the oracle is the same float64 X X^T."""
@@ -116,7 +119,7 @@ def test_hessian_token_major(ctx, n, p, dtype):
     H = ctx.build_hessian_tokens(Xg).cpu().numpy().astype(np.float64)
     check_H(H, Href, p, "token-major %s n=%d p=%d" % (str(dtype), n, p))
     assert np.array_equal(H, H.T)
-    if p >= 16:
+    if 16 <= p < 100000:
         cut = p // 3
         H2 = ctx.build_hessian_tokens(Xg[:cut])
         H2 = ctx.build_hessian_tokens(Xg[cut:], H=H2, accumulate=True).cpu().numpy().astype(np.float64)
