@@ -45,7 +45,7 @@ typedef enum {
   GANQ_OK = 0,
   GANQ_ERR_INVALID_ARG = 1,
   GANQ_ERR_UNSUPPORTED = 2,
-  GANQ_ERR_NOT_PD = 3,     /* a Cholesky pivot was <= 0 or not finite */
+  GANQ_ERR_NOT_PD = 3,     /* a Cholesky pivot was not finite or not above its threshold (ganq_cholesky) */
   GANQ_ERR_WORKSPACE = 4,  /* workspace missing or too small */
   GANQ_ERR_HIP = 5         /* HIP runtime failure; text in ganq_last_error */
 } ganq_status;
@@ -126,9 +126,14 @@ ganq_status ganq_build_hessian_tokens(ganq_ctx* ctx, const void* Xt, ganq_dtype 
 /* L = lower Cholesky factor of H (or of its preconditioned form), Eq. (10),
  * Remark 3.1, Appendix A.  L is n x n fp32 with the strict upper triangle
  * zeroed; L may not alias H.  *info_host: 0 on success, k > 0 if pivot k
- * (1-based) was <= 0 or not finite (status GANQ_ERR_NOT_PD; L is then
- * unspecified).  Under GANQ_PRECOND_AUTO a failed plain attempt is repeated
- * with DIAGDOM and *info_host reports the second attempt.  Synchronises. */
+ * (1-based) was not finite or not above 8 sqrt(n) 2^-24 times the diagonal entry
+ * of its column in the matrix being factorised (status GANQ_ERR_NOT_PD; L is
+ * then unspecified).  The threshold is the size of the rounding noise of an fp32
+ * Schur complement: a pivot below it says the matrix is singular to working
+ * precision (fewer tokens than features, duplicated features), which a float64
+ * factorisation of the same numbers may not notice; Remark 3.1 / Appendix A are
+ * the remedy.  Under GANQ_PRECOND_AUTO a failed plain attempt is repeated with
+ * DIAGDOM and *info_host reports the second attempt.  Synchronises. */
 ganq_status ganq_cholesky(ganq_ctx* ctx, const float* H, int64_t n, int64_t ldh,
                           ganq_precond precond, float lambda, float* L, int64_t ldl,
                           int64_t* info_host);

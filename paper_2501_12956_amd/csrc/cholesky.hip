@@ -21,11 +21,13 @@ __global__ void fill_i32_kernel(int* p, int v) { *p = v; }
 
 // W <- lower triangle of H (+ preconditioner on the diagonal), L <- 0.
 // delta (if used) must already hold the diagonal offsets.
+// thr[i] = pivot threshold of column i: tau times the diagonal entry that is factorised.
 __global__ __launch_bounds__(256) void copy_lower_kernel(const float* __restrict__ H, int64_t n,
                                                          int64_t ldh, float* __restrict__ W,
                                                          float* __restrict__ L, int64_t ldl,
                                                          int precond, float lambda,
-                                                         const float* __restrict__ delta) {
+                                                         const float* __restrict__ delta, float tau,
+                                                         float* __restrict__ thr) {
   const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t i = blockIdx.y;
   if (j >= n) return;
@@ -35,6 +37,8 @@ __global__ __launch_bounds__(256) void copy_lower_kernel(const float* __restrict
   if (j == i) {
     if (precond == GANQ_PRECOND_LAMBDA) v += lambda;
     if (precond == GANQ_PRECOND_DIAGDOM) v += delta[i];
+    // a diagonal that is not positive and finite fails at once (threshold +inf: no pivot passes)
+    thr[i] = (v > 0.f && v < 3.0e38f) ? tau * v : __builtin_huge_valf();
   }
   W[i * n + j] = v;
 }
@@ -108,10 +112,10 @@ template <int K>
 struct LeafSteps {
   // branch-free: a bad pivot (not positive, or not finite) is replaced by 1 and the first
   // such column of the leaf is remembered in badk
-  static __device__ inline void run(float (&a)[16], float (&rsv)[16], int r, int& badk) {
+  static __device__ inline void run(float (&a)[16], float (&rsv)[16], int r, int& badk, float thr) {
     dpp_wait(a[K]);                                   // written by the previous step's DPP FMA
     float piv = row_bcast<K>(a[K]);
-    const bool bad = !(piv > 0.f) || !(piv < 3.0e38f);
+    const bool bad = !(piv > row_bcast<K>(thr)) || !(piv < 3.0e38f);
     badk = (bad && badk == 16) ? K : badk;
     piv = bad ? 1.f : piv;
     const float rs = __builtin_amdgcn_rsqf(piv);      // 1 ulp
@@ -122,12 +126,12 @@ struct LeafSteps {
     const float nlk = -lk;
     dpp_wait(lk);
     LeafCols<K, K + 1>::update(a, lk, nlk);
-    LeafSteps<K + 1>::run(a, rsv, r, badk);
+    LeafSteps<K + 1>::run(a, rsv, r, badk, thr);
   }
 };
 template <>
 struct LeafSteps<16> {
-  static __device__ inline void run(float (&)[16], float (&)[16], int, int&) {}
+  static __device__ inline void run(float (&)[16], float (&)[16], int, int&, float) {}
 };
 
 // Forward substitution L x = e_j with one column j per lane: once x[K] is known every later
@@ -161,13 +165,16 @@ struct LeafInv<16> {
 // l holds matrix row l % 16, its 16 columns in registers); lanes 0..15 store the result.
 // Pivots and multipliers travel between lanes by DPP row broadcasts.
 __device__ inline void factor_leaf(float (*M)[BLD], float (*Inv)[BLD], int o, int nb, int64_t k0,
-                                   int* __restrict__ info) {
+                                   int* __restrict__ info, const float* __restrict__ thr) {
   const int lane = threadIdx.x & 63, r = lane & 15;
   float a[16], rsv[16], x[16];
 #pragma unroll
   for (int c = 0; c < 16; ++c) a[c] = M[o + r][o + c];
+  // lane r holds the threshold of the leaf's column r (0 for the identity padding beyond nb)
+  float th = (o + r < nb) ? thr[k0 + o + r] : 0.f;
+  dpp_wait(th);
   int badk = 16;
-  LeafSteps<0>::run(a, rsv, r, badk);
+  LeafSteps<0>::run(a, rsv, r, badk, th);
   if (badk < 16 && lane == 0 && o + badk < nb) atomicCAS(info, 0, (int)(k0 + o + badk + 1));
   // inverse of the leaf factor: lane j solves L x = e_j
 #pragma unroll
@@ -188,14 +195,14 @@ __device__ inline void factor_leaf(float (*M)[BLD], float (*Inv)[BLD], int o, in
 // matrix cores (v_mfma_f32_16x16x4_f32: lane l supplies A[l % 16][l / 16] and
 // B[l / 16][l % 16] and receives D[4 (l / 16) + r][l % 16], r = 0..3).
 __device__ inline void factor_block(float (*M)[BLD], float (*Inv)[BLD], float (*Tmp)[BLD], int nb,
-                                    int64_t k0, int* __restrict__ info) {
+                                    int64_t k0, int* __restrict__ info, const float* __restrict__ thr) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lm = lane & 15, lk = lane >> 4;
   for (int e = tid; e < NB * NB; e += 256) Inv[e >> 6][e & 63] = 0.f;
   __syncthreads();
   for (int kb = 0; kb < 4; ++kb) {
     const int o = 16 * kb;
-    if (wave == 0) factor_leaf(M, Inv, o, nb, k0, info);
+    if (wave == 0) factor_leaf(M, Inv, o, nb, k0, info, thr);
     __syncthreads();
     const int tiles = 3 - kb;             // 16-row tiles under the leaf
     // (b) P = A21 * inv(L11)^T, one row tile per wavefront, in place (a wavefront reads only
@@ -268,7 +275,8 @@ constexpr int PLD = 3 * NB + 1;   // LDS stride of the diagonal rows' earlier co
 // Workgroup w owns rows c0 + 64 + 64 w .. (if any); workgroup 0 also stores the diagonal block.
 __global__ __launch_bounds__(256) void chol_panel_kernel(const float* __restrict__ W, float* __restrict__ L,
                                                          int64_t ldl, int64_t n, int64_t J, int64_t c0,
-                                                         int nb, int* __restrict__ info) {
+                                                         int nb, int* __restrict__ info,
+                                                         const float* __restrict__ thr) {
   extern __shared__ __attribute__((aligned(16))) float psm[];
   float (*M)[BLD] = reinterpret_cast<float (*)[BLD]>(psm);
   float (*Inv)[BLD] = reinterpret_cast<float (*)[BLD]>(psm + NB * BLD);
@@ -325,7 +333,7 @@ __global__ __launch_bounds__(256) void chol_panel_kernel(const float* __restrict
       for (int r = 0; r < 4; ++r) M[16 * wave + 4 * lk + r][16 * t + lm] = acc[t][r];
   }
   __syncthreads();
-  factor_block(M, Inv, Tmp, nb, c0, info);
+  factor_block(M, Inv, Tmp, nb, c0, info, thr);
   if (blockIdx.x == 0) {
     for (int e = tid; e < NB * NB; e += 256) {
       const int rr = e >> 6, cc = e & 63;
@@ -388,14 +396,19 @@ constexpr int kOuter = 4 * NB;
 constexpr int kPanelLds = (4 * NB * BLD + NB * PLD) * (int)sizeof(float);
 
 size_t cholesky_scratch_bytes(int64_t n) {
-  return kAlign + align_up((size_t)n * sizeof(float)) + align_up((size_t)n * n * sizeof(float));
+  return kAlign + 2 * align_up((size_t)n * sizeof(float)) + align_up((size_t)n * n * sizeof(float));
 }
 
 hipError_t launch_cholesky(hipStream_t s, const float* H, int64_t n, int64_t ldh, int precond,
                            float lambda, float* L, int64_t ldl, int* info_dev) {
-  // info_dev points at scratch: [int info][pad to 256][float delta[n]][float W[n x n]]
+  // info_dev points at scratch: [int info][pad to 256][float delta[n]][float thr[n]][float W[n x n]]
   float* delta = reinterpret_cast<float*>(reinterpret_cast<char*>(info_dev) + kAlign);
-  float* W = reinterpret_cast<float*>(reinterpret_cast<char*>(delta) + align_up((size_t)n * sizeof(float)));
+  float* thr = reinterpret_cast<float*>(reinterpret_cast<char*>(delta) + align_up((size_t)n * sizeof(float)));
+  float* W = reinterpret_cast<float*>(reinterpret_cast<char*>(thr) + align_up((size_t)n * sizeof(float)));
+  // A pivot at or below tau times its column's diagonal entry is rounding noise of the fp32
+  // Schur complement (about sqrt(n) 2^-24 of that entry), not information: the matrix is then
+  // numerically singular and the factor would be useless to the S-update.
+  const float tau = 8.f * sqrtf((float)n) * 5.9604645e-8f;
   hipError_t e;
   static std::atomic<uint64_t> lds_set{0};
   if ((e = ensure_dynamic_lds((const void*)chol_panel_kernel, kPanelLds, lds_set)) != hipSuccess) return e;
@@ -406,7 +419,7 @@ hipError_t launch_cholesky(hipStream_t s, const float* H, int64_t n, int64_t ldh
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   hipLaunchKernelGGL(copy_lower_kernel, dim3((unsigned)ceil_div(n, 256), (unsigned)n), dim3(256),
-                     0, s, H, n, ldh, W, L, ldl, precond, lambda, delta);
+                     0, s, H, n, ldh, W, L, ldl, precond, lambda, delta, tau, thr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   for (int64_t J = 0; J < n; J += kOuter) {
     for (int64_t c0 = J; c0 < n && c0 < J + kOuter; c0 += NB) {
@@ -414,15 +427,18 @@ hipError_t launch_cholesky(hipStream_t s, const float* H, int64_t n, int64_t ldh
       const int64_t rem = n - c0 - NB;
       const unsigned wgs = rem > 0 ? (unsigned)ceil_div(rem, NB) : 1u;
       hipLaunchKernelGGL(chol_panel_kernel, dim3(wgs), dim3(256), kPanelLds, s, W, L, ldl, n, J, c0, nb,
-                         info_dev);
+                         info_dev, thr);
       if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     const int64_t rem = n - J - kOuter;
     if (rem <= 0) break;
     // W22 -= L21 L21^T, lower tiles only
     const float* L21 = L + (J + kOuter) * ldl + J;
-    e = launch_gemm_f32(s, /*transb=*/1, /*lower_only=*/1, rem, rem, kOuter, -1.f, L21, ldl, L21, ldl, 1.f,
-                        W + (J + kOuter) * n + (J + kOuter), n);
+    float* W22 = W + (J + kOuter) * n + (J + kOuter);
+    if ((ldl % 4) == 0 && (((uintptr_t)L21) % 16) == 0 && 128 * ldl * 4 < ((int64_t)1 << 31))
+      e = launch_syrk256_f32(s, rem, L21, ldl, W22, n);
+    else
+      e = launch_gemm_f32(s, /*transb=*/1, /*lower_only=*/1, rem, rem, kOuter, -1.f, L21, ldl, L21, ldl, 1.f, W22, n);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

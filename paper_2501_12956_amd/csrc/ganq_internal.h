@@ -149,6 +149,8 @@ hipError_t launch_gemm_f32(hipStream_t s, int transb, int lower_only, int64_t M,
                            int64_t K, float alpha, const float* A, int64_t lda, const float* B,
                            int64_t ldb, float beta, float* C, int64_t ldc);
 
+hipError_t launch_syrk256_f32(hipStream_t s, int64_t M, const float* A, int64_t lda, float* C, int64_t ldc);
+
 hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64_t p, int64_t ldx,
                               float* H, int64_t ldh, int accumulate, float* partials);
 hipError_t launch_mirror_lower(hipStream_t s, float* H, int64_t n, int64_t ldh, const float* src,

@@ -131,7 +131,186 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int lower_only, int64_t M
     }
 }
 
+
+// ---- C(lower) -= A A^T for A of exactly 256 columns: the trailing update of the blocked Cholesky ----
+//
+// The general kernel above stages 16 columns at a time and leans on several resident workgroups
+// to hide the latency of each step; with K = 256 it spends most of its time waiting.  Here the
+// whole K extent goes through LDS in four stages of 64 columns, two in flight: operand rows come
+// straight from global memory into LDS (buffer_load ... lds, 16 bytes per lane, 4 rows of 256 bytes
+// per instruction), the 16-byte chunks of a row stored at position chunk ^ (row & 15) so that a
+// 16-byte fragment read of 16 consecutive rows touches every bank once.  A lane's 16-byte read
+// supplies four MFMAs: lanes 0..31 hold columns 8g..8g+3 of their row, lanes 32..63 columns
+// 8g+4..8g+7, and v_mfma_f32_32x32x2_f32 number t multiplies element t of both (the order in which
+// the 256 products of an entry are summed does not matter).  Workgroup tile 128 x 128, four
+// wavefronts of 64 x 64; only tiles on or below the diagonal are launched.  C is read at the start
+// and the difference written at the end.
+constexpr int SK = 256;            // columns of A
+constexpr int SKS = 64;            // columns per LDS stage
+constexpr int SROWB = SKS * 4;     // bytes per LDS row
+constexpr int STILEB = 128 * SROWB;
+constexpr int SSTAGEB = 2 * STILEB;
+constexpr int SYRK_LDS = 2 * SSTAGEB;
+
+typedef int int4v __attribute__((ext_vector_type(4)));
+
+__device__ inline void syrk_load16_to_lds(int4v rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+
+__global__ __launch_bounds__(256) void syrk_f32_kernel(int64_t M, const float* __restrict__ A, int64_t lda,
+                                                       float* __restrict__ C, int64_t ldc) {
+  // tile t of the lower triangle: row bm, column bn <= bm
+  const int t = blockIdx.x;
+  int bm = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
+  while ((bm + 1) * (bm + 2) / 2 <= t) ++bm;
+  while (bm * (bm + 1) / 2 > t) --bm;
+  const int bn = t - bm * (bm + 1) / 2;
+  const int64_t m0 = (int64_t)bm * 128, n0 = (int64_t)bn * 128;
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char ssm[];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ssm;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wr = wave >> 1, wc = wave & 1;
+  const int kh = lane >> 5, l32 = lane & 31;
+
+  auto make = [&](int64_t r0) {
+    const int64_t rows = (M - r0 < 128) ? M - r0 : 128;
+    const uint64_t ad = (uint64_t)(uintptr_t)(A + r0 * lda);
+    int4v r;
+    r[0] = (int)(uint32_t)ad;
+    r[1] = (int)(uint32_t)((ad >> 32) & 0xffffu);
+    r[2] = (int)(uint32_t)(((rows - 1) * lda + SK) * 4);      // rows past the matrix read as zero
+    r[3] = 0x00020000;
+    return r;
+  };
+  const int4v rsA = make(m0), rsB = make(n0);
+
+  // one direct load: lane -> row lane / 16 of a group of 4 rows, LDS chunk position lane % 16
+  const int dr = lane >> 4, dp = lane & 15;
+  uint32_t voff[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int row = (wave + 4 * j) * 4 + dr;                 // 32 groups of 4 rows over 4 wavefronts
+    voff[j] = (uint32_t)(((int64_t)row * lda + ((dp ^ (row & 15)) * 4)) * 4);
+  }
+  auto issue = [&](int ks, int st) {
+    const uint32_t soff = (uint32_t)(ks * SKS * 4);
+    const uint32_t sb = lds0 + st * SSTAGEB;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      syrk_load16_to_lds(rsA, sb + (wave + 4 * j) * 1024, voff[j], soff);
+      syrk_load16_to_lds(rsB, sb + STILEB + (wave + 4 * j) * 1024, voff[j], soff);
+    }
+  };
+
+  issue(0, 0);
+  // the tile of C, fetched while the first operands are on their way.  A tile that lies wholly
+  // inside the matrix and strictly below the diagonal (most of them) needs no per-element tests.
+  const bool full = (m0 + 128 <= M) && (bn < bm);
+  floatx16 cin[2][2];
+  if (full) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const float* __restrict__ cp = C + (m0 + wr * 64 + i * 32 + kh * 4) * ldc + n0 + wc * 64 + j * 32 + l32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) cin[i][j][v] = cp[((v >> 2) * 8 + (v & 3)) * ldc];
+      }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int64_t col = n0 + wc * 64 + j * 32 + l32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int64_t row = m0 + wr * 64 + i * 32 + (v >> 2) * 8 + kh * 4 + (v & 3);
+          cin[i][j][v] = (row < M && col <= row) ? C[row * ldc + col] : 0.f;
+        }
+      }
+  }
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  int st = 0;
+#pragma unroll 1
+  for (int ks = 0; ks < SK / SKS; ++ks) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (ks + 1 < SK / SKS) issue(ks + 1, st ^ 1);
+    const unsigned char* As = ssm + st * SSTAGEB;
+    const unsigned char* Bs = As + STILEB;
+#pragma unroll
+    for (int g = 0; g < SKS / 8; ++g) {
+      floatx4 af[2], bf[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int row = wr * 64 + i * 32 + l32;
+        af[i] = *reinterpret_cast<const floatx4*>(As + row * SROWB + (((2 * g + kh) ^ (row & 15)) << 4));
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int row = wc * 64 + j * 32 + l32;
+        bf[j] = *reinterpret_cast<const floatx4*>(Bs + row * SROWB + (((2 * g + kh) ^ (row & 15)) << 4));
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][e], bf[j][e], acc[i][j], 0, 0, 0);
+    }
+    st ^= 1;
+  }
+
+  if (full) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        float* __restrict__ cp = C + (m0 + wr * 64 + i * 32 + kh * 4) * ldc + n0 + wc * 64 + j * 32 + l32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) cp[((v >> 2) * 8 + (v & 3)) * ldc] = cin[i][j][v] - acc[i][j][v];
+      }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int64_t col = n0 + wc * 64 + j * 32 + l32;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int64_t row = m0 + wr * 64 + i * 32 + (v >> 2) * 8 + kh * 4 + (v & 3);
+          if (row < M && col <= row) C[row * ldc + col] = cin[i][j][v] - acc[i][j][v];
+        }
+      }
+  }
+}
+
 }  // namespace
+
+// C (M x M, lower triangle) -= A A^T with A of M x 256; needs lda % 4 == 0 and a 16-byte aligned A
+// (the caller falls back to launch_gemm_f32 otherwise).
+hipError_t launch_syrk256_f32(hipStream_t s, int64_t M, const float* A, int64_t lda, float* C, int64_t ldc) {
+  if (M <= 0) return hipSuccess;
+  if ((lda % 4) != 0 || (((uintptr_t)A) % 16) != 0 || 128 * lda * 4 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+  static std::atomic<uint64_t> lds_set{0};
+  const hipError_t ea = ensure_dynamic_lds((const void*)syrk_f32_kernel, SYRK_LDS, lds_set);
+  if (ea != hipSuccess) return ea;
+  const int64_t nt = ceil_div(M, 128);
+  hipLaunchKernelGGL(syrk_f32_kernel, dim3((unsigned)(nt * (nt + 1) / 2)), dim3(256), SYRK_LDS, s, M, A, lda, C, ldc);
+  return hipGetLastError();
+}
 
 hipError_t launch_gemm_f32(hipStream_t s, int transb, int lower_only, int64_t M, int64_t N,
                            int64_t K, float alpha, const float* A, int64_t lda, const float* B,

@@ -132,7 +132,7 @@ def test_hessian_token_major(ctx, n, p, dtype):
 
 
 # ----------------------------------------------------------------------------- L
-@pytest.mark.parametrize("n", [200, 64, 65, 1, 300, 523])
+@pytest.mark.parametrize("n", [200, 64, 65, 1, 300, 523, 1000, 777, 1288])
 def test_cholesky(ctx, n):
     _, X = make_problem(4, n, max(4 * n, 64), 4, x_dtype=torch.float32, w_kind="gauss_outlier")
     H32 = (X @ X.T).contiguous()
@@ -144,6 +144,13 @@ def test_cholesky(ctx, n):
     assert np.array_equal(L, np.tril(L)) and np.all(np.diag(L) > 0)
     assert np.linalg.norm(L @ L.T - H64) <= 2e-6 * np.linalg.norm(H64)
     assert np.linalg.norm(L - Lref) <= 1e-4 * np.linalg.norm(Lref)
+    if n >= 300:
+        # a factor written into a wider array (leading dimension larger than n, not a multiple of 4
+        # for odd n: the rank-256 updates then take the general product instead of the dedicated one)
+        wide = torch.full((n, n + 5 + (n & 1)), 7.0, device="cuda")
+        L2, info = ctx.cholesky(H32.cuda(), L=wide[:, :n])
+        assert info == 0 and torch.equal(wide[:, n:], torch.full_like(wide[:, n:], 7.0))
+        assert np.linalg.norm(L2.cpu().numpy().astype(np.float64) - Lref) <= 1e-4 * np.linalg.norm(Lref)
 
 
 def test_cholesky_preconditioning_modes(ctx):
@@ -167,6 +174,36 @@ def test_cholesky_preconditioning_modes(ctx):
         Lref, _ = ref.cholesky(H64, omode, lam)
         assert np.linalg.norm(L @ L.T - Hp) <= 2e-6 * np.linalg.norm(Hp)
         assert np.linalg.norm(L - Lref) <= 1e-3 * np.linalg.norm(Lref)
+
+
+def test_cholesky_numerically_singular_is_reported(ctx):
+    """Fewer tokens than features plus a diagonal shift far below fp32 resolution: in exact (and in
+    float64) arithmetic the matrix is positive definite with pivots near 1e-9 of the diagonal, so a
+    float64 factorisation succeeds; in fp32 those pivots are rounding noise of either sign.  The
+    plain factorisation must say so (not return a factor built on noise), AUTO must fall back to the
+    preconditioner of Appendix A, and a well-conditioned matrix of the same size must pass."""
+    from paper_2501_12956_amd import binding as b
+    rng = np.random.default_rng(5)
+    n, p = 320, 300
+    X = rng.normal(size=(n, p))
+    H64 = X @ X.T
+    H64 += 1e-9 * np.diag(np.diag(H64))
+    Hg = dev(H64, torch.float32)
+    Lo, _ = ref.cholesky(H64)                     # before rounding to fp32 storage: positive definite
+    assert np.all(np.diag(Lo) > 0)
+    L, info = ctx.cholesky(Hg, b.PRECOND_NONE, raise_on_fail=False)
+    assert p < info <= n, info
+    L, info = ctx.cholesky(Hg, b.PRECOND_AUTO)
+    assert info == 0
+    Hp = ref.precondition(Hg.cpu().numpy().astype(np.float64), ref.PRECOND_DIAGDOM)
+    L = L.cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(L @ L.T - Hp) <= 2e-6 * np.linalg.norm(Hp)
+    # strongly correlated but well above the noise floor: pivots near 1e-3 of the diagonal pass
+    Y = rng.normal(size=(n, 4 * n))
+    Y[1] = Y[0] + 0.03 * Y[1]
+    G = dev(Y @ Y.T, torch.float32)
+    L, info = ctx.cholesky(G, b.PRECOND_NONE)
+    assert info == 0
 
 
 # ----------------------------------------------------------------------------- T^0
