@@ -79,8 +79,15 @@ typedef struct {
   ganq_init init;       /* used when init_codebooks != 0 */
   int init_codebooks;   /* 0: T holds T^0 on entry; 1: build T^0 from W */
   ganq_empty empty;
-  int reserved;         /* must be 0 */
+  int flags;            /* 0, or GANQ_OPT_FULL_T_UPDATE; other bits must be 0 */
 } ganq_options;
+
+/* ganq_options.flags: sum S_i H S_i^T again in every sweep.  By default a sweep that changed few
+ * indices (at most about 3.5 % of them, and at most max(256, n / 16) in any row) brings the
+ * matrices of the previous sweep up to date from the changed columns instead - the same sums in
+ * another order, kept in float64, so T^K may differ from the always-summing path in the last bits
+ * of fp32 (and so may a near-tie of a later S-update). */
+#define GANQ_OPT_FULL_T_UPDATE 1
 
 /* ---- context ------------------------------------------------------------ */
 
@@ -183,7 +190,7 @@ ganq_status ganq_layer_loss(ganq_ctx* ctx, const float* W, int64_t m, int64_t n,
  * it).  loss_history_host (optional, 2*iters doubles) receives the objective
  * after every half step (index 2k: after the S-step of sweep k, 2k+1: after
  * its T-step); passing it adds one m x n x n product per half step.
- * opts == NULL means {NONE, 0, QUANTILE_MID, 0, ZERO}.  With L == NULL the work
+ * opts == NULL means {NONE, 0, QUANTILE_MID, 0, ZERO, 0}.  With L == NULL the work
  * that does not depend on the factor (conversion of W, T^0, G = W H) runs on a
  * second stream of the context beside the factorisation and is joined before
  * the first sweep.  Synchronises. */
@@ -268,14 +275,16 @@ typedef enum {
   GANQ_K_GEMM_WH = 3,  /* G = W H, once per layer */
   GANQ_K_UPDATE_S = 4, /* one S-update sweep (one launch) */
   GANQ_K_T_PREP = 5,   /* integer digits of H for the T-update, once per layer */
-  GANQ_K_T_PAD = 6,    /* padded copy of Q, once per sweep */
+  GANQ_K_T_PAD = 6,    /* padded copy of Q (and the list of changed columns), once per sweep */
   GANQ_K_T_ACCUM = 7,  /* one-hot GEMM of the T-update, once per sweep */
   GANQ_K_T_SOLVE = 8,  /* per-row assembly and solve, once per sweep */
   GANQ_K_LOSS = 9,     /* objective evaluation */
   GANQ_K_OUTLIER = 10, /* outlier split (sort, offsets, compaction) */
   GANQ_K_PACK = 11,    /* stored form: bit packing and fp16 tables */
   GANQ_K_LUT_GEMV = 12,/* look-up-table product for one activation vector */
-  GANQ_K_COUNT = 13
+  GANQ_K_T_DELTA = 13, /* update of S_i H S_i^T from the changed columns, in sweeps with few changes */
+  GANQ_K_T_SKIP = 14,  /* launches of T_ACCUM / T_DELTA that found the other one chosen and returned */
+  GANQ_K_COUNT = 15
 } ganq_kernel_class;
 
 /* on != 0: bracket every kernel class launched through this context with HIP
@@ -285,6 +294,14 @@ ganq_status ganq_profile_enable(ganq_ctx* ctx, int on);
 /* Synchronises the stream, then writes the accumulated milliseconds and number
  * of bracketed launches per class (arrays of GANQ_K_COUNT, host memory). */
 ganq_status ganq_profile_read(ganq_ctx* ctx, double* ms_host, int64_t* launches_host);
+
+/* What the sweeps of the last ganq_quantize_layer call on this context did (host memory only, no
+ * GPU work): *sweeps_host = number of logged sweeps (at most 64; 0 if the call ran with
+ * GANQ_OPT_FULL_T_UPDATE or a single sweep), and for sweep k < min(*sweeps_host, capacity):
+ * log_host[3k] = 1 if it updated S_i H S_i^T from the changed columns, 0 if it summed it again;
+ * log_host[3k+1] = the largest number of indices that changed in one row against the sweep
+ * before; log_host[3k+2] = their total (both 0 for the first sweep).  log_host may be NULL. */
+ganq_status ganq_sweep_log(const ganq_ctx* ctx, int32_t* log_host, int capacity, int* sweeps_host);
 
 /* Rates this GPU sustains on bare loops, for roofline fractions against measured rather than
  * published peaks: peaks_host[0] = fp16 matrix-core TFLOP/s (v_mfma_f32_32x32x16_f16),

@@ -26,15 +26,16 @@ EXPORTS = ["ganq_create", "ganq_destroy", "ganq_workspace_bytes", "ganq_set_work
            "ganq_cholesky",
            "ganq_init_codebooks", "ganq_update_S", "ganq_update_T", "ganq_layer_loss",
            "ganq_quantize_layer", "ganq_outlier_split", "ganq_outlier_split_noalloc", "ganq_packed_row_bytes", "ganq_pack_layer",
-           "ganq_lut_gemv", "ganq_profile_enable", "ganq_profile_read", "ganq_measure_peaks"]
+           "ganq_lut_gemv", "ganq_profile_enable", "ganq_profile_read", "ganq_measure_peaks", "ganq_sweep_log"]
 
 KERNEL_CLASSES = ["hessian", "cholesky", "init", "gemm_wh", "update_s", "t_prep", "t_pad", "t_accum",
-                  "t_solve", "loss", "outlier", "pack", "lut_gemv"]
+                  "t_solve", "loss", "outlier", "pack", "lut_gemv", "t_delta", "t_skip"]
+OPT_FULL_T_UPDATE = 1
 
 
 class GanqOptions(ctypes.Structure):
     _fields_ = [("precond", ctypes.c_int), ("lambda_", ctypes.c_float), ("init", ctypes.c_int),
-                ("init_codebooks", ctypes.c_int), ("empty", ctypes.c_int), ("reserved", ctypes.c_int)]
+                ("init_codebooks", ctypes.c_int), ("empty", ctypes.c_int), ("flags", ctypes.c_int)]
 
 
 class GanqError(RuntimeError):
@@ -101,6 +102,8 @@ def load_library():
     lib.ganq_profile_enable.restype = ci
     lib.ganq_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     lib.ganq_profile_read.restype = ci
+    lib.ganq_sweep_log.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ci, ctypes.POINTER(ci)]
+    lib.ganq_sweep_log.restype = ci
     lib.ganq_measure_peaks.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
     lib.ganq_measure_peaks.restype = ci
     _lib = lib
@@ -181,6 +184,14 @@ class Context:
         cnt = (ctypes.c_int64 * k)()
         self._check(self.lib.ganq_profile_read(self.handle, ms, cnt))
         return {name: (ms[i], cnt[i]) for i, name in enumerate(KERNEL_CLASSES)}
+
+    def sweep_log(self):
+        """[(updated?, largest number of changed indices in a row, total changed)] per sweep of the last
+        quantize_layer call."""
+        n = ctypes.c_int(0)
+        buf = (ctypes.c_int32 * (3 * 64))()
+        self._check(self.lib.ganq_sweep_log(self.handle, buf, 64, ctypes.byref(n)))
+        return [(int(buf[3 * k]), int(buf[3 * k + 1]), int(buf[3 * k + 2])) for k in range(n.value)]
 
     def measure_peaks(self):
         """Sustained on-box rates: {"f16_mfma_tflops", "f32_mfma_tflops", "i8_mfma_tops", "copy_gbs"}."""
@@ -321,9 +332,10 @@ class Context:
         return y
 
     def quantize_layer(self, W, H, nbits, iters, T=None, L=None, precond=PRECOND_NONE, lam=0.0,
-                       init=INIT_QUANTILE_MID, empty=EMPTY_ZERO, Q=None, history=False):
+                       init=INIT_QUANTILE_MID, empty=EMPTY_ZERO, Q=None, history=False, full_t_update=False):
         m, n = W.shape
-        opts = GanqOptions(precond, lam, init, 1 if T is None else 0, empty, 0)
+        opts = GanqOptions(precond, lam, init, 1 if T is None else 0, empty,
+                           OPT_FULL_T_UPDATE if full_t_update else 0)
         if T is None:
             T = torch.empty(m, 1 << nbits, dtype=torch.float32, device=W.device)
         if Q is None:

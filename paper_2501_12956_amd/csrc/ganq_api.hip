@@ -54,7 +54,9 @@ struct ProfScope {
     return e;
   }
   // events go on the stream the bracketed kernels are launched on
-  ProfScope(ganq_ctx* c, int k, hipStream_t on = nullptr) : ctx(c), cls(k), st(on != nullptr ? on : c->stream) {
+  int tag = -1;
+  ProfScope(ganq_ctx* c, int k, hipStream_t on = nullptr, int tg = -1)
+      : ctx(c), cls(k), st(on != nullptr ? on : c->stream), tag(tg) {
     if (!c->prof_on) return;
     a = get(c);
     b = get(c);
@@ -64,7 +66,7 @@ struct ProfScope {
   ~ProfScope() {
     if (!live) return;
     if (hipEventRecord(b, st) == hipSuccess)
-      ctx->prof_pending.push_back({cls, a, b});
+      ctx->prof_pending.push_back({cls, a, b, tag});
     ctx->prof_launches[cls] += 1;
   }
 };
@@ -399,6 +401,15 @@ ganq_status ganq_profile_read(ganq_ctx* ctx, double* ms_host, int64_t* launches_
   return GANQ_OK;
 }
 
+ganq_status ganq_sweep_log(const ganq_ctx* ctx, int32_t* log_host, int capacity, int* sweeps_host) {
+  if (ctx == nullptr || sweeps_host == nullptr) return GANQ_ERR_INVALID_ARG;
+  *sweeps_host = ctx->sweep_log_len;
+  if (log_host == nullptr) return GANQ_OK;
+  for (int k = 0; k < ctx->sweep_log_len && k < capacity; ++k)
+    for (int q = 0; q < 3; ++q) log_host[3 * k + q] = ctx->sweep_log[3 * k + q];
+  return GANQ_OK;
+}
+
 ganq_status ganq_measure_peaks(ganq_ctx* ctx, double* peaks_host) {
   if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
   GANQ_REQUIRE(ctx, peaks_host != nullptr, "peaks_host");
@@ -636,19 +647,19 @@ ganq_status ganq_update_T(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, i
   }
   {
     ProfScope prof(ctx, GANQ_K_T_PREP);
-    GANQ_HIP(ctx, launch_t_prepare(s, H, m, n, ldh, nbits, scratch));
+    GANQ_HIP(ctx, launch_t_prepare(s, H, m, n, ldh, nbits, scratch, 0));
   }
   {
     ProfScope prof(ctx, GANQ_K_T_PAD);
-    GANQ_HIP(ctx, launch_t_pad(s, Q, m, n, ldq, nbits, scratch));
+    GANQ_HIP(ctx, launch_t_pad(s, Q, m, n, ldq, nbits, scratch, 0));
   }
   {
     ProfScope prof(ctx, GANQ_K_T_ACCUM);
-    GANQ_HIP(ctx, launch_t_accum(s, m, n, nbits, scratch));
+    GANQ_HIP(ctx, launch_t_accum(s, m, n, nbits, scratch, 0));
   }
   {
     ProfScope prof(ctx, GANQ_K_T_SOLVE);
-    GANQ_HIP(ctx, launch_t_solve(s, G, n, m, n, Q, ldq, nbits, (int)empty, T, empty_count, scratch));
+    GANQ_HIP(ctx, launch_t_solve(s, G, n, m, n, Q, ldq, nbits, (int)empty, T, empty_count, scratch, -1));
   }
   ctx->last_error.clear();
   return GANQ_OK;
@@ -687,7 +698,7 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   o.init = GANQ_INIT_QUANTILE_MID;
   o.init_codebooks = 0;
   o.empty = GANQ_EMPTY_ZERO;
-  o.reserved = 0;
+  o.flags = 0;
   if (opts != nullptr) o = *opts;
   GANQ_REQUIRE(ctx, dtype_ok(w_dtype), "w_dtype");
   GANQ_REQUIRE(ctx, m >= 0 && n > 0, "m, n");
@@ -697,7 +708,7 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   GANQ_REQUIRE(ctx, L == nullptr || ldl >= n, "ldl");
   GANQ_REQUIRE(ctx, m == 0 || (W != nullptr && T != nullptr && Q != nullptr), "W / T / Q");
   GANQ_REQUIRE(ctx, ldw >= n && ldq >= n, "ldw / ldq");
-  GANQ_REQUIRE(ctx, o.reserved == 0, "options.reserved must be 0");
+  GANQ_REQUIRE(ctx, (o.flags & ~GANQ_OPT_FULL_T_UPDATE) == 0, "options.flags has unknown bits");
   GANQ_REQUIRE(ctx, o.precond >= GANQ_PRECOND_NONE && o.precond <= GANQ_PRECOND_AUTO, "options.precond");
   GANQ_REQUIRE(ctx, o.precond != GANQ_PRECOND_LAMBDA || (o.lambda > 0.f && std::isfinite(o.lambda)),
                "options.lambda must be positive and finite");
@@ -734,6 +745,9 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   if (G == nullptr || s_scratch == nullptr || t_scratch == nullptr || gs == nullptr)
     return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small (solver scratch)");
 
+  // later sweeps may update S_i H S_i^T from the changed columns instead of summing it again
+  const bool incremental = (o.flags & GANQ_OPT_FULL_T_UPDATE) == 0 && iters > 1;
+  const size_t prof_first = ctx->prof_pending.size();
   hipStream_t pre = s;               // stream of the work that does not need L
   const bool forked = L == nullptr;
   if (forked) {
@@ -764,7 +778,7 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
       }
       // the integer digits of H are made once per layer
       ProfScope prof(ctx, GANQ_K_T_PREP, pre);
-      if ((e = launch_t_prepare(pre, H, m, n, ldh, nbits, t_scratch)) != hipSuccess) return e;
+      if ((e = launch_t_prepare(pre, H, m, n, ldh, nbits, t_scratch, incremental ? 1 : 0)) != hipSuccess) return e;
     }
     return hipSuccess;
   };
@@ -798,17 +812,23 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
       st = run_loss(ctx, sub, Wf, m, n, ldwf, H, ldh, T, Q, ldq, nbits, &loss_history_host[2 * k], nullptr, gs);
       if (st != GANQ_OK) return st;
     }
+    const int cur = k & 1;
     {
       ProfScope prof(ctx, GANQ_K_T_PAD);
-      GANQ_HIP(ctx, launch_t_pad(s, Q, m, n, ldq, nbits, t_scratch));
+      GANQ_HIP(ctx, launch_t_pad(s, Q, m, n, ldq, nbits, t_scratch, cur));
+      if (incremental && k > 0) GANQ_HIP(ctx, launch_t_flips(s, m, n, nbits, t_scratch, cur));
     }
     {
-      ProfScope prof(ctx, GANQ_K_T_ACCUM);
-      GANQ_HIP(ctx, launch_t_accum(s, m, n, nbits, t_scratch));
+      ProfScope prof(ctx, GANQ_K_T_ACCUM, nullptr, k);
+      GANQ_HIP(ctx, launch_t_accum(s, m, n, nbits, t_scratch, cur));
+    }
+    if (incremental && k > 0) {
+      ProfScope prof(ctx, GANQ_K_T_DELTA, nullptr, k);
+      GANQ_HIP(ctx, launch_t_delta(s, m, n, nbits, t_scratch, cur));
     }
     {
       ProfScope prof(ctx, GANQ_K_T_SOLVE);
-      GANQ_HIP(ctx, launch_t_solve(s, G, n, m, n, Q, ldq, nbits, (int)o.empty, T, nullptr, t_scratch));
+      GANQ_HIP(ctx, launch_t_solve(s, G, n, m, n, Q, ldq, nbits, (int)o.empty, T, nullptr, t_scratch, k));
     }
     if (loss_history_host != nullptr) {
       Arena sub((char*)ctx->ws + align_up(ar.off), ctx->ws_bytes - align_up(ar.off));
@@ -817,6 +837,24 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
     }
   }
   GANQ_HIP(ctx, hipStreamSynchronize(s));
+  ctx->sweep_log_len = 0;
+  if (incremental && iters > 0) {
+    // which of the two kernels ran in each sweep is known on the device only
+    const int cnt = iters < kTLogMax ? iters : kTLogMax;
+    GANQ_HIP(ctx, read_t_log(s, m, n, nbits, t_scratch, ctx->sweep_log, cnt));
+    ctx->sweep_log_len = cnt;
+    // time the other kernel's immediate return under its own class
+    for (size_t r = prof_first; r < ctx->prof_pending.size(); ++r) {
+      auto& rec = ctx->prof_pending[r];
+      if (rec.tag < 0 || rec.tag >= cnt) continue;
+      const bool delta = ctx->sweep_log[3 * rec.tag] != 0;
+      if ((rec.cls == GANQ_K_T_ACCUM && delta) || (rec.cls == GANQ_K_T_DELTA && !delta)) {
+        ctx->prof_launches[rec.cls] -= 1;
+        rec.cls = GANQ_K_T_SKIP;
+        ctx->prof_launches[GANQ_K_T_SKIP] += 1;
+      }
+    }
+  }
   ctx->last_error.clear();
   return GANQ_OK;
 }

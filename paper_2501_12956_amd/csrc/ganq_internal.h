@@ -21,13 +21,16 @@ struct ganq_ctx {
   std::string last_error;
   // optional per-kernel-class timing with HIP events on the context's stream
   bool prof_on = false;
-  struct ProfRec { int cls; hipEvent_t a, b; };
+  struct ProfRec { int cls; hipEvent_t a, b; int tag; };
   std::vector<ProfRec> prof_pending;
   std::vector<hipEvent_t> prof_free;
   double prof_ms[GANQ_K_COUNT] = {0};
   int64_t prof_launches[GANQ_K_COUNT] = {0};
   // second stream (default priority) and two events: work of one call that does not depend on
   // the factorisation runs beside it; always joined before the call returns
+  // log of the last ganq_quantize_layer call (3 ints per sweep, see read_t_log) and its length
+  int sweep_log[3 * 64] = {0};
+  int sweep_log_len = 0;
   hipStream_t side = nullptr;
   hipEvent_t fork_ev = nullptr, join_ev = nullptr;
 };
@@ -169,17 +172,29 @@ hipError_t launch_update_S(hipStream_t s, const float* W, int64_t m, int64_t n, 
                            const float* L, int64_t ldl, const float* T, int nbits, uint8_t* Q,
                            int64_t ldq, float* E, int64_t lde, void* scratch);
 
-// T-update in four steps on one scratch region: integer digits of H (once per layer), padded
-// copy of Q, the one-hot GEMM with fold epilogue, and the per-row assembly + solve
-// (G = W * H is an input, computed once per layer).
+// T-update on one scratch region: integer digits of H (once per layer), padded copy of Q, the
+// one-hot GEMM with fold epilogue, and the per-row assembly + solve (G = W * H is an input,
+// computed once per layer).  From the second sweep of a layer on, launch_t_flips lists the columns
+// whose code changed and launch_t_delta brings S_i H S_i^T up to date from them when they are few;
+// launch_t_accum and launch_t_delta are both enqueued and decide on the device which of them runs.
 hipError_t launch_t_prepare(hipStream_t s, const float* H, int64_t m, int64_t n, int64_t ldh,
-                            int nbits, void* scratch);
+                            int nbits, void* scratch, int allow_delta);
+// cur = 0 / 1: which of the two padded copies of Q is the current sweep's (the other one holds the
+// previous sweep's)
 hipError_t launch_t_pad(hipStream_t s, const uint8_t* Q, int64_t m, int64_t n, int64_t ldq,
-                        int nbits, void* scratch);
-hipError_t launch_t_accum(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch);
+                        int nbits, void* scratch, int cur);
+hipError_t launch_t_flips(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch, int cur);
+hipError_t launch_t_accum(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch, int cur);
+hipError_t launch_t_delta(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch, int cur);
+// sweep: index of the alternation (0 for a stand-alone T-update); the choice made in it is logged
 hipError_t launch_t_solve(hipStream_t s, const float* G, int64_t ldg, int64_t m, int64_t n,
                           const uint8_t* Q, int64_t ldq, int nbits, int empty_mode, float* T,
-                          int32_t* empty_count, void* scratch);
+                          int32_t* empty_count, void* scratch, int sweep);
+// log[3 k .. 3 k + 2] = {1 if sweep k updated S_i H S_i^T from the changed columns, 0 if it summed
+// it; the largest number of changed indices in a row; their total} (device to host copy of the log
+// kept in scratch; synchronises)
+constexpr int kTLogMax = 64;
+hipError_t read_t_log(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch, int* modes_host, int count);
 
 // row_loss[i] = sum_j F_ij * E_ij with E = W - T[Q] written to Ebuf first (launch_residual),
 // F = E * H by launch_gemm_split, then launch_rowdot.

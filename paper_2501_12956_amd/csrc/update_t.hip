@@ -34,6 +34,17 @@
 // M_i per group of row tiles of H go to scratch and are summed in float64 by the solve
 // kernel, which also forms D_i and b_i, drops unused codes (pseudo-inverse reading: their
 // entry is 0, or kept) and solves the reduced system by Cholesky in float64.
+//
+// Later sweeps of Algorithm 1 change few indices (a few per cent from the fifth sweep on the
+// synthetic layers), and S_i H0 S_i^T (H0 = H without its diagonal) can then be brought up to
+// date instead of being summed again: with D = S_new - S_old (two entries per changed column)
+//   A_new - A_old = D (H0 S_new^T) + (D (H0 S_old^T))^T,
+// which needs, for each changed column j of row i only, the sums of row j of H0 by the new and by
+// the old codes: |changed| n additions per row instead of n^2 / 2.  The rows of H are gathered by
+// index, so nothing is shared between the rows of W and the cost is the bytes of H that move: the
+// update pays off below about 3.5 % changed indices (t_delta_kernel; the choice is made on the
+// device, per sweep, from the counts of the kernel that lists the changes).  The state A_i is kept
+// in float64 and every change is an exact integer sum scaled by a power of two.
 #include "ganq_internal.h"
 
 namespace ganq {
@@ -119,8 +130,8 @@ __device__ __host__ inline bool tile_shared_acc(int flags) {
   return (flags & ((flags & TF_THREE) ? TF_SUM3 : TF_SUM2)) == 0;
 }
 
-// Row j: the largest |H_jk| 2^-e_k over k < j gives the row exponents for two and for three
-// digits; the row asks for three digits unless 16 of its largest scaled entry stay below
+// Row j: the largest |H_jk| 2^-e_k over k != j (the update of later sweeps reads whole rows)
+// gives the row exponents for two and for three digits; the row asks for three digits unless 16 of its largest scaled entry stay below
 // sqrt(H_jj) g (a unit of its 16-bit integers is then at most 2^-19 sqrt(H_jj H_kk) for
 // every live column k), and sum_k |H_jk| 2^s tells whether any subset sum of the row's integers
 // (times their column factors) stays inside an int32.
@@ -130,12 +141,14 @@ __global__ __launch_bounds__(256) void t_rowscale_kernel(const float* __restrict
                                                          const uint8_t* __restrict__ Cs,
                                                          int8_t* __restrict__ S2,
                                                          int8_t* __restrict__ S3,
+                                                         int16_t* __restrict__ Sneed,
                                                          int* __restrict__ Ptile) {
   __shared__ float rmx[256], rsum[256];
   const int64_t j = blockIdx.x;
   float mx = 0.f, sum = 0.f;
   if (j < n) {
-    for (int64_t k = threadIdx.x; k < j; k += 256) {
+    for (int64_t k = threadIdx.x; k < n; k += 256) {
+      if (k == j) continue;
       const float a = fabsf(H[j * ldh + k]);
       sum += a;
       mx = fmaxf(mx, a / (float)Cs[k]);
@@ -155,6 +168,7 @@ __global__ __launch_bounds__(256) void t_rowscale_kernel(const float* __restrict
   mx = rmx[0];
   sum = rsum[0];
   int s2 = 0, s3 = 0;
+  int need = -30000;          // smallest two-digit exponent that is precise enough; none for an empty row
   if (mx > 0.f && mx < __builtin_huge_valf()) {
     s2 = 14 - ilogbf(mx);
     if (ldexpf(mx, s2) > V2MAX) --s2;
@@ -172,55 +186,112 @@ __global__ __launch_bounds__(256) void t_rowscale_kernel(const float* __restrict
     const int flags = (two ? 0 : TF_THREE) | (three ? 0 : TF_FOUR) | (s2 <= t ? 0 : TF_SUM2) |
                       (s3 <= t ? 0 : TF_SUM3);
     if (flags != 0) atomicOr(&Ptile[j / TM], flags);
+    if (yard > 0.f) need = 18 - ilogbf(yard);       // 2^-s <= 2^-18 yard, the bound that `two` tests
   }
   S2[j] = (int8_t)s2;
   S3[j] = (int8_t)s3;
+  Sneed[j] = (int16_t)need;
 }
 
-// Hs[digit][j][k], digit 0 the most significant one; only the tiles the GEMM reads
+// Hs[digit][j][k], digit 0 the most significant one: whole rows, k != j (the diagonal entry is 0;
+// it enters through D_i).  The GEMM of a full sweep visits k < j only: it reads the tiles left of
+// the diagonal tile from Hs and the diagonal tile itself from Hd[digit][tile][j % TM][k % TM],
+// which holds the same digits for k < j and zeros elsewhere.
 __global__ __launch_bounds__(256) void t_split_kernel(const float* __restrict__ H, int64_t n,
                                                       int64_t ldh, int64_t npad,
                                                       const uint8_t* __restrict__ Cs,
                                                       const int8_t* __restrict__ S2,
                                                       const int8_t* __restrict__ S3,
                                                       const int* __restrict__ Ptile,
-                                                      int8_t* __restrict__ Hs,
+                                                      int8_t* __restrict__ Hs, int8_t* __restrict__ Hd,
                                                       float* __restrict__ Wj) {
   const int64_t j = blockIdx.y;                                   // row of H
   const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;      // column
   if (k >= npad) return;
-  if (k / TM > j / TM) return;
   const int P = tile_digits(Ptile[j / TM]);
   const int sj = (j < n) ? ((P == 2) ? S2[j] : (P == 3) ? S3[j] : S3[j] + 8) : 0;
   if (k == 0) Wj[j] = ldexpf(1.f, -sj);
   int iv = 0;
-  if (j < n && k < j) {
+  if (j < n && k < n && k != j) {
     const float lim = (P == 2) ? V2MAX : (P == 3) ? V3MAX : 256.f * V3MAX;
     float v = rintf(ldexpf(H[j * ldh + k], sj) / (float)Cs[k]);
     v = (v == v) ? fminf(fmaxf(v, -lim), lim) : 0.f;
     iv = (int)v;
   }
-  const int d0 = (int)(int8_t)(iv & 0xff);
-  const int v1 = (iv - d0) >> 8;
-  const int64_t o = j * npad + k, ps = npad * npad;
-  if (P == 2) {
-    Hs[o] = (int8_t)v1;
-    Hs[ps + o] = (int8_t)d0;
-  } else {
-    const int d1 = (int)(int8_t)(v1 & 0xff);
-    const int v2 = (v1 - d1) >> 8;
-    if (P == 3) {
-      Hs[o] = (int8_t)v2;
-      Hs[ps + o] = (int8_t)d1;
-      Hs[2 * ps + o] = (int8_t)d0;
-    } else {
-      const int d2 = (int)(int8_t)(v2 & 0xff);
-      Hs[o] = (int8_t)((v2 - d2) >> 8);
-      Hs[ps + o] = (int8_t)d2;
-      Hs[2 * ps + o] = (int8_t)d1;
-      Hs[3 * ps + o] = (int8_t)d0;
+  int dgt[4] = {0, 0, 0, 0};            // most significant first, P of them
+  {
+    int rest = iv;
+    for (int q = P - 1; q >= 0; --q) {
+      const int d = (int)(int8_t)(rest & 0xff);
+      dgt[q] = d;
+      rest = (rest - d) >> 8;
     }
   }
+  const int64_t o = j * npad + k, ps = npad * npad;
+  for (int q = 0; q < P; ++q) Hs[q * ps + o] = (int8_t)dgt[q];
+  if (k / TM == j / TM) {
+    const int64_t od = ((j / TM) * TM + (j % TM)) * TM + (k % TM), pd = npad * TM;
+    for (int q = 0; q < P; ++q) Hd[q * pd + od] = (int8_t)((k < j) ? dgt[q] : 0);
+  }
+}
+
+// May later sweeps update A_i instead of summing it again?  An update adds and removes whole rows
+// of the integer matrix, entries right of the diagonal included, while a sweep that sums visits
+// each pair once, left of the diagonal: the two agree exactly only if the integers are symmetric,
+// v_jk 2^(e_k - s_j) = v_kj 2^(e_j - s_k), i.e. s_j = s - e_j with one s for the whole matrix.  That
+// choice is made here when it costs no precision - every tile at two digits, s the largest value
+// that keeps every row inside 16 bits, and every row still as fine as the two-digit rule asks -
+// and then the update is allowed; otherwise the per-row exponents stay and every sweep sums.
+__global__ __launch_bounds__(1024) void t_symscale_kernel(const int* __restrict__ Ptile, int mtiles, int64_t n,
+                                                          int allow, const uint8_t* __restrict__ Cs,
+                                                          int8_t* __restrict__ S2,
+                                                          const int16_t* __restrict__ Sneed,
+                                                          int* __restrict__ Tstat) {
+  __shared__ int red[1024];
+  const int tid = threadIdx.x;
+  int smin = 1 << 20;
+  for (int64_t j = tid; j < n; j += 1024)
+    if (Sneed[j] > -30000) smin = min(smin, (int)S2[j] + (31 - __builtin_clz((unsigned)Cs[j])));
+  red[tid] = smin;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) {
+    if (tid < w) red[tid] = min(red[tid], red[tid + w]);
+    __syncthreads();
+  }
+  smin = red[0];
+  __syncthreads();
+  int bad = 0;
+  for (int t = tid; t < mtiles; t += 1024)
+    if (Ptile[t] & (TF_THREE | TF_FOUR)) bad = 1;
+  for (int64_t j = tid; j < n; j += 1024) {
+    const int sj = smin - (31 - __builtin_clz((unsigned)Cs[j]));
+    if (sj < (int)Sneed[j] || sj < -120 || sj > 110) bad = 1;
+  }
+  red[tid] = bad;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) {
+    if (tid < w) red[tid] |= red[tid + w];
+    __syncthreads();
+  }
+  const int ok = (allow != 0 && red[0] == 0 && smin < (1 << 20)) ? 1 : 0;
+  if (ok)
+    for (int64_t j = tid; j < n; j += 1024) S2[j] = (int8_t)(smin - (31 - __builtin_clz((unsigned)Cs[j])));
+  if (tid == 0) {
+    Tstat[0] = 0;
+    Tstat[1] = 0;
+    Tstat[2] = 0;       // no state yet
+    Tstat[3] = ok;
+    Tstat[4] = 0;
+  }
+}
+
+// Tstat: [0] largest number of changed indices in a row, [1] their total, [2] A-state valid,
+// [3] updates allowed for this layer, [4] number of 64-column chunks of changed columns.  The same
+// test in every kernel of a sweep: update when at most 1 / kDeltaInv of the indices changed.
+constexpr int kDeltaInv = 24;
+constexpr int kDeltaChunk = 32;
+__device__ inline bool t_use_delta(const int* __restrict__ st, int64_t m, int64_t n, int fmax) {
+  return st[2] != 0 && st[3] != 0 && st[0] <= fmax && (int64_t)st[1] * kDeltaInv <= m * n;
 }
 
 // Zero-padded copy of Q (Qp, one byte per index, read by the fold) and, for the one-hot
@@ -240,6 +311,250 @@ __global__ __launch_bounds__(256) void pad_q_kernel(const uint8_t* __restrict__ 
   Qo[i * npad + k] = (uint16_t)(nrow * TK + ((((kk >> 4) ^ (nrow >> 1)) & 3) << 4) + (kk & 15));
 }
 
+// ---- changed indices of a sweep ----
+// Row i: the columns whose code differs between the previous padded copy of Q and the current one,
+// in ascending order, as j | old << 16 | new << 20 (at most fmax are stored; Fcnt holds the true
+// count).
+__global__ __launch_bounds__(256) void t_flips_kernel(const uint8_t* __restrict__ Qn,
+                                                      const uint8_t* __restrict__ Qo, int64_t npad,
+                                                      int fmax, uint32_t* __restrict__ Flist,
+                                                      int* __restrict__ Fcnt) {
+  __shared__ int wcnt[4];
+  const int64_t i = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int base = 0;
+  // 16 columns per thread and round (npad is a multiple of 128, so a thread's 16 are all inside or
+  // all outside the row); the order inside a round is thread, then column
+  for (int64_t k0 = 0; k0 < npad; k0 += 4096) {
+    const int64_t k = k0 + 16 * tid;
+    uint4 qn = uint4{0u, 0u, 0u, 0u}, qo = uint4{0u, 0u, 0u, 0u};
+    if (k < npad) {
+      qn = *reinterpret_cast<const uint4*>(Qn + i * npad + k);
+      qo = *reinterpret_cast<const uint4*>(Qo + i * npad + k);
+    }
+    const uint32_t wn[4] = {qn.x, qn.y, qn.z, qn.w}, wo[4] = {qo.x, qo.y, qo.z, qo.w};
+    int mine = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t x = wn[w] ^ wo[w];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) mine += ((x >> (8 * b)) & 0xffu) != 0u;
+    }
+    // exclusive prefix of `mine` over the workgroup
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int t = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += t;
+    }
+    if (lane == 63) wcnt[wave] = incl;
+    __syncthreads();
+    int woff = 0, total = 0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      woff += (v < wave) ? wcnt[v] : 0;
+      total += wcnt[v];
+    }
+    int pos = base + woff + incl - mine;
+    if (mine > 0) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const uint32_t cn = (wn[w] >> (8 * b)) & 0xffu, co = (wo[w] >> (8 * b)) & 0xffu;
+          if (cn != co) {
+            if (pos < fmax) Flist[i * fmax + pos] = (uint32_t)(k + 4 * w + b) | (co << 16) | (cn << 20);
+            ++pos;
+          }
+        }
+    }
+    base += total;
+    __syncthreads();
+  }
+  if (tid == 0) Fcnt[i] = base;
+}
+
+// Cbase[i] = number of 32-column chunks of changed columns in rows before i (exclusive prefix sum
+// over the rows, one workgroup), Tstat[4] = their total: one wavefront of the update kernel per
+// chunk.  Also the largest count of a row and the total (Tstat[0], Tstat[1]), and the mark that a
+// completed sweep has left a valid state (Tstat[2]; this kernel runs from the second sweep on).
+__global__ __launch_bounds__(1024) void t_chunks_kernel(const int* __restrict__ Fcnt, int64_t m, int fmax,
+                                                        int* __restrict__ Cbase, int* __restrict__ Tstat) {
+  __shared__ int part[1024], pmax[1024], ptot[1024];
+  const int tid = threadIdx.x;
+  const int64_t per = (m + 1023) / 1024;
+  const int64_t b = tid * per, e = (b + per < m) ? b + per : m;
+  auto chunks = [&](int c) {
+    if (c > fmax) c = fmax;         // such a sweep sums again anyway; keep the table in range
+    return (c + kDeltaChunk - 1) / kDeltaChunk;
+  };
+  int s = 0, mx = 0, tot = 0;
+  for (int64_t i = b; i < e; ++i) {
+    const int c = Fcnt[i];
+    s += chunks(c);
+    mx = max(mx, c);
+    tot += c;
+  }
+  part[tid] = s;
+  pmax[tid] = mx;
+  ptot[tid] = tot;
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0, gmax = 0, gtot = 0;
+    for (int t = 0; t < 1024; ++t) {
+      const int v = part[t];
+      part[t] = run;
+      run += v;
+      gmax = max(gmax, pmax[t]);
+      gtot += ptot[t];
+    }
+    Tstat[0] = gmax;
+    Tstat[1] = gtot;
+    Tstat[2] = 1;
+    Tstat[4] = run;
+    Cbase[m] = run;
+  }
+  __syncthreads();
+  int run = part[tid];
+  for (int64_t i = b; i < e; ++i) {
+    Cbase[i] = run;
+    run += chunks(Fcnt[i]);
+  }
+}
+
+typedef int int4v __attribute__((ext_vector_type(4)));
+typedef int intx16 __attribute__((ext_vector_type(16)));
+
+// 16 one-hot operand bytes: byte t of word w is cs (the column factor 2^e_k) where the code byte
+// equals b, else 0.  Codes and b are below 16: 0x10 - (code ^ b) has bit 4 set exactly on a match.
+__device__ inline int4v onehot16(uint4 q, uint32_t brep, uint4 cs) {
+  auto one = [&](uint32_t qw, uint32_t cw) -> int {
+    const uint32_t hit = (0x10101010u - (qw ^ brep)) & 0x10101010u;   // 0x10 per matching byte
+    uint32_t msk = hit >> 4;                                          // 0x01
+    msk |= msk << 1;
+    msk |= msk << 2;
+    msk |= msk << 4;                                                  // 0xff
+    return (int)(cw & msk);
+  };
+  int4v r;
+  r[0] = one(q.x, cs.x);
+  r[1] = one(q.y, cs.y);
+  r[2] = one(q.z, cs.z);
+  r[3] = one(q.w, cs.w);
+  return r;
+}
+
+// ---- update of A_i for the changed columns of a sweep ----
+// One wavefront per chunk of 32 changed columns j of a row i (rows differ widely in how many of
+// their indices still change, so the unit of work is the chunk, not the row): one MFMA row tile of
+// 32 gathered rows of Hs; the 32 columns of the product are the 16 old codes and the 16 new codes
+// (one-hot operands built in registers from the two padded copies of Q), each digit of H in its own
+// int32 accumulator:  Z[j, c] = sum_k v_jk 2^e_k [code_k == c]  exactly.  Then, with d_j = e_new(j) -
+// e_old(j) and w_j = 2^-s_j, the chunk's share of
+//   A[a, b] += sum_j d_j[a] w_j Znew[j, b] + sum_j d_j[b] w_j Zold[j, a]
+// is accumulated per lane in float64 (a lane owns one column of Z, i.e. one b or one a) and written
+// to the chunk's slot of Dpart; the solve kernel adds a row's slots to its state in a fixed order.
+// The kernel is bound by the latency of the gathered loads, so it is kept small enough in registers
+// for four wavefronts per SIMD.
+#ifndef T_DB
+#define T_DB 4
+#endif
+#ifndef T_DWAVES
+#define T_DWAVES 4
+#endif
+constexpr int DB = T_DB;        // npad is a multiple of 128 = 32 * 4; DB = 4 or a divisor
+template <int NBITS>
+__global__ __launch_bounds__(256, T_DWAVES) void t_delta_kernel(const int8_t* __restrict__ Hs, int64_t npad,
+                                                         const uint8_t* __restrict__ Qnew,
+                                                         const uint8_t* __restrict__ Qold,
+                                                         const uint8_t* __restrict__ Cs,
+                                                         const float* __restrict__ Wj,
+                                                         const uint32_t* __restrict__ Flist,
+                                                         const int* __restrict__ Fcnt,
+                                                         const int* __restrict__ Cbase,
+                                                         const int* __restrict__ Tstat, int fmax,
+                                                         int64_t m, int64_t n,
+                                                         double* __restrict__ Dpart) {
+  constexpr int C = 1 << NBITS;
+  __shared__ double Rs[4][64][C + 1];
+  if (!t_use_delta(Tstat, m, n, fmax)) return;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q = (int)blockIdx.x * 4 + wave;      // chunk number
+  if (q >= Tstat[4]) return;
+  // row of this chunk: the last i with Cbase[i] <= q (Cbase is non-decreasing, Cbase[m] = total)
+  int lo = 0, hi = (int)m;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (Cbase[mid] <= q) lo = mid; else hi = mid;
+  }
+  const int64_t i = lo;
+  const int t0 = (q - Cbase[lo]) * kDeltaChunk;
+  const int cnt = Fcnt[i];
+  const int c = lane & 31, kh = lane >> 5;
+  const uint32_t brep = 0x01010101u * (uint32_t)(c & 15);
+  const uint8_t* __restrict__ qrow = ((c < 16) ? Qold : Qnew) + i * npad + 16 * kh;
+  const uint8_t* __restrict__ csrow = Cs + 16 * kh;
+  const int64_t ps = npad * npad;
+
+  const int e0 = t0 + c;
+  const uint32_t ent = (e0 < cnt) ? Flist[i * fmax + e0] : 0u;
+  const int64_t jrow = ent & 0xffffu;
+  const float wrow = (e0 < cnt) ? Wj[jrow] : 0.f;       // rows beyond the count add nothing
+  const int8_t* __restrict__ hrow = Hs + jrow * npad + 16 * kh;
+  intx16 acc[2];
+#pragma unroll
+  for (int d = 0; d < 2; ++d)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[d][v] = 0;
+  // DB k-steps (128-byte lines of every gathered row and digit) are fetched before use
+  for (int64_t k0 = 0; k0 < npad; k0 += 32 * DB) {
+    int4v a[DB][2];
+    uint4 q16[DB], cs16[DB];
+#pragma unroll
+    for (int t = 0; t < DB; ++t) {
+#pragma unroll
+      for (int d = 0; d < 2; ++d) a[t][d] = *reinterpret_cast<const int4v*>(hrow + d * ps + k0 + 32 * t);
+      q16[t] = *reinterpret_cast<const uint4*>(qrow + k0 + 32 * t);
+      cs16[t] = *reinterpret_cast<const uint4*>(csrow + k0 + 32 * t);
+    }
+#pragma unroll
+    for (int t = 0; t < DB; ++t) {
+      const int4v bf = onehot16(q16[t], brep, cs16[t]);
+#pragma unroll
+      for (int d = 0; d < 2; ++d) acc[d] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t][d], bf, acc[d], 0, 0, 0);
+    }
+  }
+  // fold: row r of the tile sits in register v = 4 (r / 8) + r % 4 of the lanes with kh = (r / 4) % 2
+  double R[C];
+#pragma unroll
+  for (int a2 = 0; a2 < C; ++a2) R[a2] = 0.0;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) {
+    const int v = 4 * (r >> 3) + (r & 3), khr = (r >> 2) & 1;
+    const uint32_t er = (uint32_t)__builtin_amdgcn_readlane((int)ent, r);
+    const float wr = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wrow), r));
+    const double z = (double)acc[0][v] * 256.0 + (double)acc[1][v];
+    const double x = (kh == khr) ? (double)wr * z : 0.0;
+    const int ao = (int)((er >> 16) & 15u), an = (int)((er >> 20) & 15u);
+#pragma unroll
+    for (int a2 = 0; a2 < C; ++a2) {
+      const double f = (double)((an == a2) - (ao == a2));     // scalar: -1, 0 or 1
+      R[a2] = fma(f, x, R[a2]);
+    }
+  }
+  // the chunk's A[a, b]: R of the lanes that own column "new b", element a, plus R of the lanes
+  // that own column "old a", element b (two lanes each: kh = 0, 1)
+#pragma unroll
+  for (int a2 = 0; a2 < C; ++a2) Rs[wave][lane][a2] = R[a2];
+  __builtin_amdgcn_wave_barrier();
+  for (int e = lane; e < C * C; e += 64) {
+    const int a2 = e / C, b2 = e % C;
+    Dpart[(int64_t)q * C * C + e] =
+        (Rs[wave][16 + b2][a2] + Rs[wave][48 + b2][a2]) + (Rs[wave][a2][b2] + Rs[wave][32 + a2][b2]);
+  }
+}
+
 // ---- the GEMM with fold epilogue ----
 // LDS: T_S stages of { A tile: TM rows x 64 bytes (one digit of 64 k), one-hot B tile: TN rows
 // x 64 bytes }.  A tiles arrive by direct-to-LDS buffer loads; such a load writes 64 x 16
@@ -254,9 +569,6 @@ constexpr int T_ATILEB = TM * T_ROWB;
 constexpr int T_BTILEB = TN * T_ROWB;
 constexpr int T_STAGEB = T_ATILEB + T_BTILEB;
 constexpr int T_LDS_BYTES = T_S * T_STAGEB;
-
-typedef int int4v __attribute__((ext_vector_type(4)));
-typedef int intx16 __attribute__((ext_vector_type(16)));
 
 // One wavefront-wide direct load: lane l's 16 bytes land at LDS byte lds_addr + 16 l.  The
 // compiler does not see these loads; the kernel waits for them (vmcnt) before the barrier
@@ -285,6 +597,9 @@ template <int V> struct IntC { static constexpr int value = V; };
 // C x C blocks of the 16 x 16 result are meaningful; the others are never stored.
 template <int NBITS>
 __global__ __launch_bounds__(64 * TNW, 2) void t_accum_kernel(const int8_t* __restrict__ Hs,
+                                                           const int8_t* __restrict__ Hd,
+                                                           const int* __restrict__ Tstat, int fmax,
+                                                           int64_t m_rows, int64_t n_cols,
                                                            int64_t npad, const uint8_t* __restrict__ Qp,
                                                            const uint16_t* __restrict__ Qo,
                                                            const uint8_t* __restrict__ Cs,
@@ -292,6 +607,8 @@ __global__ __launch_bounds__(64 * TNW, 2) void t_accum_kernel(const int8_t* __re
                                                            const int* __restrict__ Ptile,
                                                            int64_t mpad, int mtiles, int ngroups,
                                                            float* __restrict__ Apart) {
+  // a sweep that updates A_i from the changed columns does not sum it again
+  if (t_use_delta(Tstat, m_rows, n_cols, fmax)) return;
   constexpr int C = 1 << NBITS;
   constexpr int RW = TN >> NBITS;             // rows i per workgroup
   constexpr int EPT = (RW * TK) / (64 * TNW); // one-hot positions per thread and stage
@@ -352,9 +669,12 @@ __global__ __launch_bounds__(64 * TNW, 2) void t_accum_kernel(const int8_t* __re
   constexpr int ALD = (TM / 16) / TNW;
   const int dr = lane >> 2;
   const int dc = (lane & 3) ^ ((dr >> 1) & 3);
-  uint32_t voff[ALD];
+  uint32_t voff[ALD], voffd[ALD];      // in a row tile of Hs (row stride npad) and in a diagonal tile of Hd (TM)
 #pragma unroll
-  for (int a = 0; a < ALD; ++a) voff[a] = (uint32_t)((int64_t)((wave + TNW * a) * 16 + dr) * npad + dc * 16);
+  for (int a = 0; a < ALD; ++a) {
+    voff[a] = (uint32_t)((int64_t)((wave + TNW * a) * 16 + dr) * npad + dc * 16);
+    voffd[a] = (uint32_t)(((wave + TNW * a) * 16 + dr) * TM + dc * 16);
+  }
 
   const int rswz = (l32 >> 1) & 3;
   // per-lane LDS byte offsets of the fragments inside a stage
@@ -437,18 +757,31 @@ __global__ __launch_bounds__(64 * TNW, 2) void t_accum_kernel(const int8_t* __re
     const int acmp = lane & (C - 1);
 
     for (int dg = 0; dg < P; ++dg) {
-      int4v rsA;
+      int4v rsA, rsD;
       {
         const uint64_t ad = (uint64_t)(uintptr_t)(Hs + ((int64_t)dg * npad + jt0) * npad);
         rsA[0] = (int)(uint32_t)ad;
         rsA[1] = (int)(uint32_t)((ad >> 32) & 0xffffu);
         rsA[2] = (int)(uint32_t)((int64_t)TM * npad);
         rsA[3] = 0x00020000;
+        const uint64_t dd = (uint64_t)(uintptr_t)(Hd + ((int64_t)dg * npad + jt0) * TM);
+        rsD[0] = (int)(uint32_t)dd;
+        rsD[1] = (int)(uint32_t)((dd >> 32) & 0xffffu);
+        rsD[2] = (int)(uint32_t)(TM * TM);
+        rsD[3] = 0x00020000;
       }
+      // the last two k-steps are the diagonal tile, whose copy in Hd is zero for k >= j
       auto issue = [&](int k, int st) {
+        if (k < nk - TM / TK) {
 #pragma unroll
-        for (int a = 0; a < ALD; ++a)
-          load16_to_lds(rsA, lds0 + st * T_STAGEB + (wave + TNW * a) * 1024, voff[a], (uint32_t)k * (uint32_t)TK);
+          for (int a = 0; a < ALD; ++a)
+            load16_to_lds(rsA, lds0 + st * T_STAGEB + (wave + TNW * a) * 1024, voff[a], (uint32_t)k * (uint32_t)TK);
+        } else {
+#pragma unroll
+          for (int a = 0; a < ALD; ++a)
+            load16_to_lds(rsD, lds0 + st * T_STAGEB + (wave + TNW * a) * 1024, voffd[a],
+                          (uint32_t)(k - (nk - TM / TK)) * (uint32_t)TK);
+        }
       };
       if (dg > 0 && shared_acc) {
         // next digit: everything so far moves up by one digit
@@ -569,6 +902,10 @@ __global__ __launch_bounds__(64 * TNW, 2) void t_accum_kernel(const int8_t* __re
 
 // ---- per-row assembly and solve (one wavefront per row, float64) ----
 __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ Apart, int ngroups,
+                                                     const int* __restrict__ Tstat, int fmax, int64_t m_rows,
+                                                     double* __restrict__ Astate, int* __restrict__ Tlog,
+                                                     const int* __restrict__ Cbase,
+                                                     const double* __restrict__ Dpart,
                                                      int64_t mpad, const float* __restrict__ scale,
                                                      const float* __restrict__ Hdiag,
                                                      const float* __restrict__ G, int64_t ldg,
@@ -631,10 +968,17 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
     dead[tid] = (c0 == 0);
   }
   __syncthreads();
-  const double inv_s = (double)scale[1];
-  // M = sum of the per-group partial folds (coalesced reads); then A = (M + M^T) / s + Diag(D)
+  // Off-diagonal part S_i H0 S_i^T: after a sweep that summed it, M + M^T with M the sum of the
+  // per-group partial folds (coalesced reads), which also becomes the state that later sweeps
+  // update; after a sweep that updated it, the state itself.
+  const bool from_state = t_use_delta(Tstat, m_rows, n, fmax);
+  if (Tlog != nullptr && i == 0 && tid == 0) {
+    Tlog[0] = from_state ? 1 : 0;
+    Tlog[1] = Tstat[0];
+    Tlog[2] = Tstat[1];
+  }
   __shared__ double Ms[16][17];
-  {
+  if (!from_state) {
     const int64_t gs = mpad * C * C;
     // all loads of up to 16 groups x 4 entries are issued before the first is used: one round
     // trip to memory instead of one per four groups
@@ -675,7 +1019,19 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
   __syncthreads();
   for (int e = tid; e < C * C; e += 64) {
     const int a = e / C, b = e % C;
-    double v = (Ms[a][b] + Ms[b][a]) * inv_s;
+    double v;
+    if (from_state) {
+      // the state of the sweep before plus this sweep's chunks of changed columns, in order
+      v = Astate[i * C * C + e];
+      const int c0 = Cbase[i], c1 = Cbase[i + 1];
+      if (c1 > c0) {
+        for (int cc = c0; cc < c1; ++cc) v += Dpart[(int64_t)cc * C * C + e];
+        Astate[i * C * C + e] = v;
+      }
+    } else {
+      v = Ms[a][b] + Ms[b][a];
+      Astate[i * C * C + e] = v;
+    }
     if (a == b) { v += Dg[a]; diag0[a] = v; }
     A[a][b] = v;
   }
@@ -774,12 +1130,30 @@ struct TScratch {
   float* Wj;
   int8_t* S2;
   int8_t* S3;
+  int16_t* Sneed;
   int* Ptile;
   int8_t* Hs;
-  uint8_t* Qp;
+  int8_t* Hd;
+  uint8_t* Qp[2];       // padded copies of Q of the current and of the previous sweep
   uint16_t* Qo;
   float* Apart;
+  uint32_t* Flist;      // changed columns per row (fmax each)
+  int* Fcnt;
+  int* Tstat;
+  int* Cbase;           // chunks of changed columns before each row (mpad + 1)
+  double* Astate;       // S_i H0 S_i^T per row, the state that later sweeps update
+  double* Dpart;        // one C x C slot per chunk of changed columns
+  int64_t max_chunks;
+  int fmax;
 };
+
+// most changed columns per row that a sweep may update instead of summing A_i again
+inline int t_fmax(int64_t npad) {
+  int64_t f = ceil_div(npad / 2, 32) * 32;      // rows settle at very different speeds: leave room
+  if (f < 256) f = 256;
+  if (f > 16384) f = 16384;
+  return (int)f;
+}
 
 inline size_t t_layout(int64_t m, int64_t n, int nbits, char* base, TScratch* out) {
   const int64_t npad = t_npad(n), mpad = t_mpad(m, nbits);
@@ -792,11 +1166,23 @@ inline size_t t_layout(int64_t m, int64_t n, int nbits, char* base, TScratch* ou
   const size_t o_wj = take((size_t)npad * sizeof(float));
   const size_t o_s2 = take((size_t)npad);
   const size_t o_s3 = take((size_t)npad);
+  const size_t o_sn = take((size_t)npad * sizeof(int16_t));
   const size_t o_pt = take((size_t)(npad / TM) * sizeof(int));
   const size_t o_hs = take((size_t)TP * npad * npad);
+  const size_t o_hd = take((size_t)TP * npad * TM);
   const size_t o_q = take((size_t)mpad * npad);
+  const size_t o_q2 = take((size_t)mpad * npad);
   const size_t o_qo = take((size_t)mpad * npad * sizeof(uint16_t));
   const size_t o_ap = take((size_t)t_groups(n) * mpad * C * C * sizeof(float));
+  const int fmax = t_fmax(npad);
+  const size_t o_fl = take((size_t)mpad * fmax * sizeof(uint32_t));
+  const size_t o_fc = take((size_t)mpad * sizeof(int));
+  const size_t o_ts = take((8 + 3 * kTLogMax) * sizeof(int));   // counters, then (choice, max, total) per sweep
+  const size_t o_as = take((size_t)mpad * C * C * sizeof(double));
+  const size_t o_cb = take((size_t)(mpad + 1) * sizeof(int));
+  // a sweep is updated only when at most m n / kDeltaInv indices changed
+  const int64_t max_chunks = (m * n / kDeltaInv) / kDeltaChunk + m + 1;
+  const size_t o_dp = take((size_t)max_chunks * C * C * sizeof(double));
   if (out != nullptr) {
     out->scale = (float*)(base + o_scale);
     out->Hdiag = (float*)(base + o_diag);
@@ -804,11 +1190,22 @@ inline size_t t_layout(int64_t m, int64_t n, int nbits, char* base, TScratch* ou
     out->Wj = (float*)(base + o_wj);
     out->S2 = (int8_t*)(base + o_s2);
     out->S3 = (int8_t*)(base + o_s3);
+    out->Sneed = (int16_t*)(base + o_sn);
     out->Ptile = (int*)(base + o_pt);
     out->Hs = (int8_t*)(base + o_hs);
-    out->Qp = (uint8_t*)(base + o_q);
+    out->Hd = (int8_t*)(base + o_hd);
+    out->Qp[0] = (uint8_t*)(base + o_q);
+    out->Qp[1] = (uint8_t*)(base + o_q2);
     out->Qo = (uint16_t*)(base + o_qo);
     out->Apart = (float*)(base + o_ap);
+    out->Flist = (uint32_t*)(base + o_fl);
+    out->Fcnt = (int*)(base + o_fc);
+    out->Tstat = (int*)(base + o_ts);
+    out->Astate = (double*)(base + o_as);
+    out->Cbase = (int*)(base + o_cb);
+    out->Dpart = (double*)(base + o_dp);
+    out->max_chunks = max_chunks;
+    out->fmax = fmax;
   }
   return off;
 }
@@ -819,10 +1216,10 @@ size_t update_t_scratch_bytes(int64_t m, int64_t n, int nbits) {
   return t_layout(m, n, nbits, nullptr, nullptr);
 }
 
-// integer digits of the strictly lower triangle of H and their scale factors into scratch (once
-// per layer)
+// integer digits of H and their scale factors into scratch (once per layer); allow_delta says
+// whether later sweeps of this layer may update A_i from the changed columns
 hipError_t launch_t_prepare(hipStream_t s, const float* H, int64_t m, int64_t n, int64_t ldh,
-                            int nbits, void* scratch) {
+                            int nbits, void* scratch, int allow_delta) {
   TScratch sc;
   t_layout(m, n, nbits, (char*)scratch, &sc);
   const int64_t npad = t_npad(n);
@@ -831,28 +1228,47 @@ hipError_t launch_t_prepare(hipStream_t s, const float* H, int64_t m, int64_t n,
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(t_rowscale_kernel, dim3((unsigned)n), dim3(256), 0, s, H, n, ldh, sc.scale, sc.Hdiag,
-                     sc.Cs, sc.S2, sc.S3, sc.Ptile);
+                     sc.Cs, sc.S2, sc.S3, sc.Sneed, sc.Ptile);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // the index j of a changed column is stored in 16 bits
+  hipLaunchKernelGGL(t_symscale_kernel, dim3(1), dim3(1024), 0, s, sc.Ptile, (int)(npad / TM), n,
+                     (allow_delta != 0 && npad <= 65536) ? 1 : 0, sc.Cs, sc.S2, sc.Sneed, sc.Tstat);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(t_split_kernel, dim3((unsigned)ceil_div(npad, 256), (unsigned)npad), dim3(256), 0, s,
-                     H, n, ldh, npad, sc.Cs, sc.S2, sc.S3, sc.Ptile, sc.Hs, sc.Wj);
+                     H, n, ldh, npad, sc.Cs, sc.S2, sc.S3, sc.Ptile, sc.Hs, sc.Hd, sc.Wj);
   return hipGetLastError();
 }
 
-// zero-padded aligned copy of Q into scratch
+// zero-padded aligned copy of Q into buffer `cur` (0 or 1) of scratch
 hipError_t launch_t_pad(hipStream_t s, const uint8_t* Q, int64_t m, int64_t n, int64_t ldq,
-                        int nbits, void* scratch) {
+                        int nbits, void* scratch, int cur) {
   TScratch sc;
   t_layout(m, n, nbits, (char*)scratch, &sc);
   const int64_t npad = t_npad(n), mpad = t_mpad(m, nbits);
   hipLaunchKernelGGL(pad_q_kernel, dim3((unsigned)ceil_div(npad, 256), (unsigned)mpad), dim3(256), 0,
-                     s, Q, m, n, ldq, npad, nbits, sc.Qp, sc.Qo);
+                     s, Q, m, n, ldq, npad, nbits, sc.Qp[cur & 1], sc.Qo);
+  return hipGetLastError();
+}
+
+// columns that changed between the padded copy of the previous sweep (buffer 1 - cur) and the
+// current one (buffer cur), per row, with their maximum and total
+hipError_t launch_t_flips(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch, int cur) {
+  TScratch sc;
+  t_layout(m, n, nbits, (char*)scratch, &sc);
+  const int64_t npad = t_npad(n), mpad = t_mpad(m, nbits);
+  hipLaunchKernelGGL(t_flips_kernel, dim3((unsigned)mpad), dim3(256), 0, s, sc.Qp[cur & 1], sc.Qp[(cur & 1) ^ 1],
+                     npad, sc.fmax, sc.Flist, sc.Fcnt);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(t_chunks_kernel, dim3(1), dim3(1024), 0, s, sc.Fcnt, m, sc.fmax, sc.Cbase, sc.Tstat);
   return hipGetLastError();
 }
 
 // partial M_i = sum_{j>k} [Q_ij = a][Q_ik = b] H_jk per group of row tiles (the one-hot GEMM)
 template <int NBITS>
-static hipError_t launch_t_accum_n(hipStream_t s, int64_t m, int64_t n, void* scratch) {
+static hipError_t launch_t_accum_n(hipStream_t s, int64_t m, int64_t n, void* scratch, int cur) {
   TScratch sc;
   t_layout(m, n, NBITS, (char*)scratch, &sc);
   const int64_t npad = t_npad(n), mpad = t_mpad(m, NBITS);
@@ -866,29 +1282,62 @@ static hipError_t launch_t_accum_n(hipStream_t s, int64_t m, int64_t n, void* sc
   }
   const int64_t total = (mpad / (TN >> NBITS)) * groups;
   hipLaunchKernelGGL(t_accum_kernel<NBITS>, dim3((unsigned)(8 * ceil_div(total, 8))), dim3(64 * TNW),
-                     shmem, s, sc.Hs, npad, sc.Qp, sc.Qo, sc.Cs, sc.Wj, sc.Ptile, mpad, mtiles, groups, sc.Apart);
+                     shmem, s, sc.Hs, sc.Hd, sc.Tstat, sc.fmax, m, n, npad, sc.Qp[cur & 1], sc.Qo, sc.Cs, sc.Wj,
+                     sc.Ptile, mpad, mtiles, groups, sc.Apart);
   return hipGetLastError();
 }
 
-hipError_t launch_t_accum(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch) {
+hipError_t launch_t_accum(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch, int cur) {
   switch (nbits) {
-    case 1: return launch_t_accum_n<1>(s, m, n, scratch);
-    case 2: return launch_t_accum_n<2>(s, m, n, scratch);
-    case 3: return launch_t_accum_n<3>(s, m, n, scratch);
-    default: return launch_t_accum_n<4>(s, m, n, scratch);
+    case 1: return launch_t_accum_n<1>(s, m, n, scratch, cur);
+    case 2: return launch_t_accum_n<2>(s, m, n, scratch, cur);
+    case 3: return launch_t_accum_n<3>(s, m, n, scratch, cur);
+    default: return launch_t_accum_n<4>(s, m, n, scratch, cur);
+  }
+}
+
+// A_i state += the effect of the changed columns (does nothing in a sweep that sums A_i again)
+template <int NBITS>
+static hipError_t launch_t_delta_n(hipStream_t s, int64_t m, int64_t n, void* scratch, int cur) {
+  TScratch sc;
+  t_layout(m, n, NBITS, (char*)scratch, &sc);
+  const int64_t npad = t_npad(n);
+  hipLaunchKernelGGL(t_delta_kernel<NBITS>, dim3((unsigned)ceil_div(sc.max_chunks, 4)), dim3(256), 0, s, sc.Hs,
+                     npad, sc.Qp[cur & 1], sc.Qp[(cur & 1) ^ 1], sc.Cs, sc.Wj, sc.Flist, sc.Fcnt, sc.Cbase, sc.Tstat,
+                     sc.fmax, m, n, sc.Dpart);
+  return hipGetLastError();
+}
+
+hipError_t launch_t_delta(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch, int cur) {
+  switch (nbits) {
+    case 1: return launch_t_delta_n<1>(s, m, n, scratch, cur);
+    case 2: return launch_t_delta_n<2>(s, m, n, scratch, cur);
+    case 3: return launch_t_delta_n<3>(s, m, n, scratch, cur);
+    default: return launch_t_delta_n<4>(s, m, n, scratch, cur);
   }
 }
 
 // assemble A_i, b_i and solve; G = W H
 hipError_t launch_t_solve(hipStream_t s, const float* G, int64_t ldg, int64_t m, int64_t n,
                           const uint8_t* Q, int64_t ldq, int nbits, int empty_mode, float* T,
-                          int32_t* empty_count, void* scratch) {
+                          int32_t* empty_count, void* scratch, int sweep) {
   TScratch sc;
   t_layout(m, n, nbits, (char*)scratch, &sc);
   const int64_t mpad = t_mpad(m, nbits);
-  hipLaunchKernelGGL(t_solve_kernel, dim3((unsigned)m), dim3(64), 0, s, sc.Apart, t_groups(n), mpad,
-                     sc.scale, sc.Hdiag, G, ldg, Q, ldq, n, nbits, empty_mode, T, empty_count);
+  int* tlog = (sweep >= 0 && sweep < kTLogMax) ? sc.Tstat + 8 + 3 * sweep : nullptr;
+  hipLaunchKernelGGL(t_solve_kernel, dim3((unsigned)m), dim3(64), 0, s, sc.Apart, t_groups(n), sc.Tstat, sc.fmax,
+                     m, sc.Astate, tlog, sc.Cbase, sc.Dpart, mpad, sc.scale, sc.Hdiag, G, ldg, Q, ldq, n, nbits,
+                     empty_mode, T, empty_count);
   return hipGetLastError();
+}
+
+hipError_t read_t_log(hipStream_t s, int64_t m, int64_t n, int nbits, void* scratch, int* modes_host, int count) {
+  TScratch sc;
+  t_layout(m, n, nbits, (char*)scratch, &sc);
+  if (count > kTLogMax) count = kTLogMax;
+  hipError_t e = hipMemcpyAsync(modes_host, sc.Tstat + 8, (size_t)count * 3 * sizeof(int), hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return e;
+  return hipStreamSynchronize(s);
 }
 
 }  // namespace ganq

@@ -95,9 +95,9 @@ def test_argument_checks_run_on_the_host(lib):
     assert lib.ganq_update_T(h, fake, 4, 8, 8, fake, 8, None, 8, 4, 0, fake, None) == inv
     assert lib.ganq_layer_loss(h, fake, 4, 8, 8, fake, 8, fake, fake, 8, 4, None, None) == inv
     assert lib.ganq_layer_loss(h, fake, 4, -1, 8, fake, 8, fake, fake, 8, 4, ctypes.byref(loss), None) == inv
-    opts = b.GanqOptions(0, 0.0, 0, 0, 0, 1)
+    opts = b.GanqOptions(0, 0.0, 0, 0, 0, 2)
     assert lib.ganq_quantize_layer(h, fake, 1, 4, 8, 8, fake, 8, None, 0, 4, 1, ctypes.byref(opts),
-                                   fake, fake, 8, None) == inv                       # reserved != 0
+                                   fake, fake, 8, None) == inv                       # unknown flag bit
     assert lib.ganq_quantize_layer(h, fake, 1, 4, 8, 8, fake, 8, None, 0, 4, -1, None,
                                    fake, fake, 8, None) == inv
     # deployment calls: stored-form geometry, alignment, CSR arrays all or none

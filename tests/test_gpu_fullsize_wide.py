@@ -139,7 +139,11 @@ def solver_checks(ctx, name, cfg, nbits, W, Wf, H, L, H64, L64, rows, rt, Ws, ro
     TK, QK = ctx.quantize_layer(W, H, nbits, K)
     Tprev, _ = ctx.quantize_layer(W, H, nbits, K - 1)
     Tr, Qr = ctx.quantize_layer(W, H, nbits, 1, T=Tprev.clone())
-    assert torch.equal(Tr, TK) and torch.equal(Qr, QK)          # K = (K - 1) + 1, bit for bit
+    # K = (K - 1) + 1: the same Q^K bit for bit; T^K agrees to rounding (the one-call run may have
+    # updated S_i H S_i^T in its last sweep, the restarted one sums it afresh)
+    assert torch.equal(Qr, QK)
+    dT = (Tr - TK).abs().amax(dim=1) / TK.abs().amax(dim=1)
+    assert float(dT.max()) <= 1e-5
     QKs = QK[rt].cpu().numpy()
     Tps = Tprev[rt].cpu().numpy().astype(np.float64)
     TKs = TK[rt].cpu().numpy().astype(np.float64)
