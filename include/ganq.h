@@ -175,6 +175,18 @@ ganq_status ganq_update_T(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, i
                           const float* H, int64_t ldh, const uint8_t* Q, int64_t ldq, int nbits,
                           ganq_empty empty, float* T, int32_t* empty_count);
 
+/* Optional: the per-layer inputs of ganq_update_T that do not depend on Q - G = W H and the
+ * integer digits of H - computed once and kept at the start of the workspace, so that a caller who
+ * drives the alternation of Algorithm 1 itself pays for them once per layer and not once per sweep.
+ * Later ganq_update_T calls on this context with the same W, ldw, H, ldh, m, n, nbits use them; any
+ * other arguments are served as without this call.  The other calls of this header keep the
+ * prepared inputs intact (their scratch goes behind them; ganq_workspace_bytes leaves room) except
+ * ganq_quantize_layer, ganq_build_hessian_tokens and ganq_set_workspace, which drop them.  The
+ * library does not watch W or H: after changing their contents, call this again.  W == NULL and
+ * H == NULL drops what was prepared.  Asynchronous on the context's stream. */
+ganq_status ganq_update_T_prepare(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                                  const float* H, int64_t ldh, int nbits);
+
 /* Objective of Eq. (1) in the form of Eq. (9): sum_i E_i H E_i^T with
  * E = W - T[Q].  *loss_host receives the total (float64 reduction of fp32
  * row values); row_loss (optional, m fp32, device) the per-row values.

@@ -24,7 +24,7 @@ EMPTY_ZERO, EMPTY_KEEP = 0, 1
 EXPORTS = ["ganq_create", "ganq_destroy", "ganq_workspace_bytes", "ganq_set_workspace",
            "ganq_status_string", "ganq_last_error", "ganq_build_hessian", "ganq_build_hessian_tokens",
            "ganq_cholesky",
-           "ganq_init_codebooks", "ganq_update_S", "ganq_update_T", "ganq_layer_loss",
+           "ganq_init_codebooks", "ganq_update_S", "ganq_update_T", "ganq_update_T_prepare", "ganq_layer_loss",
            "ganq_quantize_layer", "ganq_outlier_split", "ganq_outlier_split_noalloc", "ganq_packed_row_bytes", "ganq_pack_layer",
            "ganq_lut_gemv", "ganq_profile_enable", "ganq_profile_read", "ganq_measure_peaks", "ganq_sweep_log"]
 
@@ -86,6 +86,8 @@ def load_library():
     lib.ganq_update_S.restype = ci
     lib.ganq_update_T.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, i64, ci, ci, vp, vp]
     lib.ganq_update_T.restype = ci
+    lib.ganq_update_T_prepare.argtypes = [vp, vp, i64, i64, i64, vp, i64, ci]
+    lib.ganq_update_T_prepare.restype = ci
     lib.ganq_layer_loss.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp, vp, i64, ci,
                                     ctypes.POINTER(ctypes.c_double), vp]
     lib.ganq_layer_loss.restype = ci
@@ -255,6 +257,17 @@ class Context:
                                            _rowmajor(L, "L"), _ptr(T), nbits, _ptr(Q),
                                            _rowmajor(Q, "Q"), _ptr(E), n if want_E else 0))
         return (Q, E) if want_E else Q
+
+    def update_T_prepare(self, W, H, nbits):
+        """Computes what ganq_update_T needs from W and H alone once; later update_T calls with the same
+        tensors reuse it.  W=None, H=None drops it."""
+        if W is None and H is None:
+            self._check(self.lib.ganq_update_T_prepare(self.handle, None, 0, 0, 0, None, 0, nbits))
+            return
+        m, n = W.shape
+        self.reserve(m, n, 0, nbits)
+        self._check(self.lib.ganq_update_T_prepare(self.handle, _ptr(W), m, n, _rowmajor(W, "W"), _ptr(H),
+                                                   _rowmajor(H, "H"), nbits))
 
     def update_T(self, W, H, Q, T, nbits, empty=EMPTY_ZERO, want_counts=False):
         m, n = W.shape

@@ -106,6 +106,19 @@ size_t quantize_scratch_bytes(int64_t m, int64_t n, int nbits) {
   return b + 8 * kAlign;
 }
 
+// Scratch arena of a stand-alone call: behind the prepared T-update inputs when they are valid and
+// `need` bytes still fit there, else from the start of the workspace (which drops the prepared inputs).
+Arena call_arena(ganq_ctx* ctx, size_t need) {
+  Arena ar(ctx->ws, ctx->ws_bytes);
+  if (ctx->tprep.valid) {
+    if (ctx->tprep.ws == ctx->ws && align_up(ctx->tprep.bytes) + need + 2 * kAlign <= ctx->ws_bytes)
+      ar.off = align_up(ctx->tprep.bytes);
+    else
+      ctx->tprep.valid = false;
+  }
+  return ar;
+}
+
 // row losses -> host double; scratch = [E][F][row values][double]
 ganq_status run_loss(ganq_ctx* ctx, Arena& ar, const float* W, int64_t m, int64_t n, int64_t ldw,
                      const float* H, int64_t ldh, const float* T, const uint8_t* Q, int64_t ldq,
@@ -222,7 +235,7 @@ ganq_status outlier_split_impl(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype,
     // 0..m-1), so nothing left by a previous call has to be cleared
     GANQ_HIP(ctx, static_outlier_scratch(ctx->device, &scratch));
   } else {
-    Arena ar(ctx->ws, ctx->ws_bytes);
+    Arena ar = call_arena(ctx, outlier_scratch_bytes(m));
     scratch = ar.take(outlier_scratch_bytes(m));
     if (scratch == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the outlier split");
   }
@@ -293,7 +306,9 @@ size_t ganq_workspace_bytes(int64_t m, int64_t n, int64_t p_tokens, int nbits) {
     const size_t ht = align_up((size_t)n * pc * sizeof(float)) + hp + 4 * kAlign;
     if (ht > h) h = ht;
   }
-  return q > h ? q : h;
+  // the prepared inputs of a stand-alone T-update stay in front of any other call's scratch
+  const size_t keep = (m > 0) ? align_up((size_t)m * n * sizeof(float)) + update_t_scratch_bytes(m, n, nbits) + 4 * kAlign : 0;
+  return q > keep + h ? q : keep + h;
 }
 
 ganq_status ganq_set_workspace(ganq_ctx* ctx, void* dev_ptr, size_t bytes) {
@@ -302,6 +317,7 @@ ganq_status ganq_set_workspace(ganq_ctx* ctx, void* dev_ptr, size_t bytes) {
   GANQ_REQUIRE(ctx, ((uintptr_t)dev_ptr) % kAlign == 0, "workspace must be 256-byte aligned");
   ctx->ws = dev_ptr;
   ctx->ws_bytes = bytes;
+  ctx->tprep.valid = false;
   ctx->last_error.clear();
   return GANQ_OK;
 }
@@ -484,7 +500,8 @@ ganq_status ganq_build_hessian(ganq_ctx* ctx, const void* X, ganq_dtype x_dtype,
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
   hipStream_t s = ctx->stream;
-  Arena ar(ctx->ws, ctx->ws_bytes);
+  Arena ar = call_arena(ctx, x_dtype == GANQ_F16 ? hessian_scratch_bytes(n, p > 0 ? p : 1)
+                                                 : (size_t)n * n * sizeof(float));
   ProfScope prof(ctx, GANQ_K_HESSIAN);
   if (x_dtype == GANQ_F16) {
     float* part = (float*)ar.take(hessian_scratch_bytes(n, p > 0 ? p : 1));
@@ -517,6 +534,7 @@ ganq_status ganq_build_hessian_tokens(ganq_ctx* ctx, const void* Xt, ganq_dtype 
   // Tokens per transposed chunk: what the workspace holds beyond the scratch of the product
   // (at least kTokenChunk, which ganq_workspace_bytes guarantees; a larger workspace means
   // fewer, larger products).
+  ctx->tprep.valid = false;          // this call sizes its chunks by the whole workspace
   const int64_t p8 = (p + 7) / 8 * 8;
   const size_t part_bytes = (x_dtype == GANQ_F16) ? hessian_scratch_bytes(n, p8) : (size_t)n * n * sizeof(float);
   int64_t chunk = p8 < kTokenChunk ? p8 : kTokenChunk;
@@ -567,7 +585,7 @@ ganq_status ganq_cholesky(ganq_ctx* ctx, const float* H, int64_t n, int64_t ldh,
   if (n > kMaxDim) return fail(ctx, GANQ_ERR_UNSUPPORTED, "n must not exceed 65535");
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
-  Arena ar(ctx->ws, ctx->ws_bytes);
+  Arena ar = call_arena(ctx, cholesky_scratch_bytes(n));
   st = run_cholesky(ctx, ar, H, n, ldh, precond, lambda, L, ldl, info_host);
   if (st == GANQ_OK) ctx->last_error.clear();
   return st;
@@ -609,13 +627,52 @@ ganq_status ganq_update_S(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, i
   if (m == 0) return GANQ_OK;
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
-  Arena ar(ctx->ws, ctx->ws_bytes);
+  Arena ar = call_arena(ctx, update_s_scratch_bytes(m, n));
   void* scratch = ar.take(update_s_scratch_bytes(m, n));
   if (scratch == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the S-update");
   {
     ProfScope prof(ctx, GANQ_K_UPDATE_S);
     GANQ_HIP(ctx, launch_update_S(ctx->stream, W, m, n, ldw, L, ldl, T, nbits, Q, ldq, E, lde, scratch));
   }
+  ctx->last_error.clear();
+  return GANQ_OK;
+}
+
+ganq_status ganq_update_T_prepare(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, int64_t ldw,
+                                  const float* H, int64_t ldh, int nbits) {
+  if (ctx == nullptr) return GANQ_ERR_INVALID_ARG;
+  ctx->tprep.valid = false;
+  if (W == nullptr && H == nullptr) {          // drop what was prepared
+    ctx->last_error.clear();
+    return GANQ_OK;
+  }
+  GANQ_REQUIRE(ctx, m > 0 && n > 0, "m, n");
+  GANQ_REQUIRE(ctx, nbits_ok(nbits), "nbits must be in [1, 4]");
+  GANQ_REQUIRE(ctx, H != nullptr && ldh >= n, "H / ldh");
+  GANQ_REQUIRE(ctx, W != nullptr && ldw >= n, "W / ldw");
+  if (m > kMaxDim || n > kMaxDim) return fail(ctx, GANQ_ERR_UNSUPPORTED, "m and n must not exceed 65535");
+  ganq_status st = bind_device(ctx);
+  if (st != GANQ_OK) return st;
+  Arena ar(ctx->ws, ctx->ws_bytes);
+  float* G = (float*)ar.take((size_t)m * n * sizeof(float));
+  void* scratch = ar.take(update_t_scratch_bytes(m, n, nbits));
+  const size_t keep = ar.off;                   // what stays between calls
+  void* gs = ar.take(gemm_split_scratch_bytes(m, n, n));
+  if (G == nullptr || scratch == nullptr || gs == nullptr)
+    return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the T-update");
+  hipStream_t s = ctx->stream;
+  {
+    ProfScope prof(ctx, GANQ_K_GEMM_WH);
+    GANQ_HIP(ctx, launch_gemm_split(s, m, n, n, W, ldw, H, ldh, G, n, gs, 0));
+  }
+  {
+    ProfScope prof(ctx, GANQ_K_T_PREP);
+    GANQ_HIP(ctx, launch_t_prepare(s, H, m, n, ldh, nbits, scratch, 0));
+  }
+  auto& tp = ctx->tprep;
+  tp.W = W; tp.H = H; tp.ldw = ldw; tp.ldh = ldh; tp.m = m; tp.n = n; tp.nbits = nbits;
+  tp.ws = ctx->ws; tp.bytes = keep; tp.G = G; tp.t_scratch = scratch;
+  tp.valid = true;
   ctx->last_error.clear();
   return GANQ_OK;
 }
@@ -634,20 +691,31 @@ ganq_status ganq_update_T(ganq_ctx* ctx, const float* W, int64_t m, int64_t n, i
   if (m > kMaxDim || n > kMaxDim) return fail(ctx, GANQ_ERR_UNSUPPORTED, "m and n must not exceed 65535");
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
-  Arena ar(ctx->ws, ctx->ws_bytes);
-  float* G = (float*)ar.take((size_t)m * n * sizeof(float));
-  void* scratch = ar.take(update_t_scratch_bytes(m, n, nbits));
-  void* gs = ar.take(gemm_split_scratch_bytes(m, n, n));
-  if (G == nullptr || scratch == nullptr || gs == nullptr)
-    return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the T-update");
   hipStream_t s = ctx->stream;
-  {
-    ProfScope prof(ctx, GANQ_K_GEMM_WH);
-    GANQ_HIP(ctx, launch_gemm_split(s, m, n, n, W, ldw, H, ldh, G, n, gs, 0));
-  }
-  {
-    ProfScope prof(ctx, GANQ_K_T_PREP);
-    GANQ_HIP(ctx, launch_t_prepare(s, H, m, n, ldh, nbits, scratch, 0));
+  float* G = nullptr;
+  void* scratch = nullptr;
+  const auto& tp = ctx->tprep;
+  if (tp.valid && tp.ws == ctx->ws && tp.W == (const void*)W && tp.H == (const void*)H && tp.ldw == ldw &&
+      tp.ldh == ldh && tp.m == m && tp.n == n && tp.nbits == nbits) {
+    // G = W H and the digits of H were left in the workspace by ganq_update_T_prepare
+    G = tp.G;
+    scratch = tp.t_scratch;
+  } else {
+    Arena ar = call_arena(ctx, align_up((size_t)m * n * sizeof(float)) + update_t_scratch_bytes(m, n, nbits) +
+                                   gemm_split_scratch_bytes(m, n, n) + 4 * kAlign);
+    G = (float*)ar.take((size_t)m * n * sizeof(float));
+    scratch = ar.take(update_t_scratch_bytes(m, n, nbits));
+    void* gs = ar.take(gemm_split_scratch_bytes(m, n, n));
+    if (G == nullptr || scratch == nullptr || gs == nullptr)
+      return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for the T-update");
+    {
+      ProfScope prof(ctx, GANQ_K_GEMM_WH);
+      GANQ_HIP(ctx, launch_gemm_split(s, m, n, n, W, ldw, H, ldh, G, n, gs, 0));
+    }
+    {
+      ProfScope prof(ctx, GANQ_K_T_PREP);
+      GANQ_HIP(ctx, launch_t_prepare(s, H, m, n, ldh, nbits, scratch, 0));
+    }
   }
   {
     ProfScope prof(ctx, GANQ_K_T_PAD);
@@ -680,7 +748,7 @@ ganq_status ganq_layer_loss(ganq_ctx* ctx, const float* W, int64_t m, int64_t n,
   if (m > kMaxDim || n > kMaxDim) return fail(ctx, GANQ_ERR_UNSUPPORTED, "m and n must not exceed 65535");
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
-  Arena ar(ctx->ws, ctx->ws_bytes);
+  Arena ar = call_arena(ctx, loss_scratch_bytes(m, n) + gemm_split_scratch_bytes(m, n, n) + 4 * kAlign);
   st = run_loss(ctx, ar, W, m, n, ldw, H, ldh, T, Q, ldq, nbits, loss_host, row_loss);
   if (st == GANQ_OK) ctx->last_error.clear();
   return st;
@@ -723,6 +791,7 @@ ganq_status ganq_quantize_layer(ganq_ctx* ctx, const void* W, ganq_dtype w_dtype
   ganq_status st = bind_device(ctx);
   if (st != GANQ_OK) return st;
   hipStream_t s = ctx->stream;
+  ctx->tprep.valid = false;          // the driver lays out the whole workspace itself
   Arena ar(ctx->ws, ctx->ws_bytes);
 
   // all scratch is carved before the first launch: with the factorisation done here, the work

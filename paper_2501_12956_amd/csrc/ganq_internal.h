@@ -31,6 +31,20 @@ struct ganq_ctx {
   // log of the last ganq_quantize_layer call (3 ints per sweep, see read_t_log) and its length
   int sweep_log[3 * 64] = {0};
   int sweep_log_len = 0;
+  // Per-layer inputs of the stand-alone T-update kept at the start of the workspace between calls
+  // (ganq_update_T_prepare): G = W H, the integer digits of H and their scratch.  While valid, the
+  // other stand-alone calls carve their scratch behind these `bytes`.
+  struct TPrep {
+    bool valid = false;
+    const void* W = nullptr;
+    const void* H = nullptr;
+    int64_t ldw = 0, ldh = 0, m = 0, n = 0;
+    int nbits = 0;
+    void* ws = nullptr;
+    size_t bytes = 0;
+    float* G = nullptr;
+    void* t_scratch = nullptr;
+  } tprep;
   hipStream_t side = nullptr;
   hipEvent_t fork_ev = nullptr, join_ev = nullptr;
 };

@@ -456,15 +456,9 @@ __device__ inline int4v onehot16(uint4 q, uint32_t brep, uint4 cs) {
 // to the chunk's slot of Dpart; the solve kernel adds a row's slots to its state in a fixed order.
 // The kernel is bound by the latency of the gathered loads, so it is kept small enough in registers
 // for four wavefronts per SIMD.
-#ifndef T_DB
-#define T_DB 4
-#endif
-#ifndef T_DWAVES
-#define T_DWAVES 4
-#endif
-constexpr int DB = T_DB;        // npad is a multiple of 128 = 32 * 4; DB = 4 or a divisor
+constexpr int DB = 4;           // k-steps fetched together: one 128-byte line per gathered row and digit
 template <int NBITS>
-__global__ __launch_bounds__(256, T_DWAVES) void t_delta_kernel(const int8_t* __restrict__ Hs, int64_t npad,
+__global__ __launch_bounds__(256, 4) void t_delta_kernel(const int8_t* __restrict__ Hs, int64_t npad,
                                                          const uint8_t* __restrict__ Qnew,
                                                          const uint8_t* __restrict__ Qold,
                                                          const uint8_t* __restrict__ Cs,

@@ -311,6 +311,56 @@ def test_update_T_stagewise(ctx, m, n, nbits):
     assert np.array_equal(cnt.cpu().numpy(), cref)
 
 
+def test_update_T_prepared_inputs(ctx):
+    """ganq_update_T_prepare leaves G = W H and the digits of H in the workspace: the T-updates (and
+    the S-updates and loss evaluations between them) of a caller-driven alternation then give bit for
+    bit what the unprepared calls give, at lower cost; after H changes in place a new prepare call
+    brings the results into line with the new H."""
+    m, n, nbits = 48, 320, 4
+    W, X = make_problem(m, n, 2048, nbits)
+    Wg = W.cuda()
+    H = ctx.build_hessian(X.cuda())
+    L, info = ctx.cholesky(H)
+    assert info == 0
+    T0 = ctx.init_codebooks(Wg, nbits)
+
+    def alternate(prepared):
+        T = T0.clone()
+        outs = []
+        if prepared:
+            ctx.update_T_prepare(Wg, H, nbits)
+        ctx.profile_enable(True)
+        for _ in range(3):
+            Q = ctx.update_S(Wg, L, T, nbits)
+            T = ctx.update_T(Wg, H, Q, T, nbits)
+            outs.append((Q.clone(), T.clone(), ctx.layer_loss(Wg, H, T, Q, nbits)))
+        prof = ctx.profile_read()
+        ctx.profile_enable(False)
+        ctx.update_T_prepare(None, None, nbits)
+        return outs, prof
+
+    plain, prof_plain = alternate(False)
+    prep, prof_prep = alternate(True)
+    assert prof_plain["gemm_wh"][1] == 3 and prof_plain["t_prep"][1] == 3
+    assert prof_prep["gemm_wh"][1] == 0 and prof_prep["t_prep"][1] == 0      # prepared outside the bracket
+    for (Qa, Ta, la), (Qb, Tb, lb) in zip(plain, prep):
+        assert torch.equal(Qa, Qb) and torch.equal(Ta, Tb) and la == lb
+    # H changes in place: prepare again, and the result is that of the new H
+    Q = plain[-1][0]
+    H2 = H.clone()
+    ctx.update_T_prepare(Wg, H2, nbits)
+    Told = ctx.update_T(Wg, H2, Q, T0.clone(), nbits)
+    H2 *= 1.0 + 0.5 * torch.eye(n, device="cuda")            # another matrix in the same memory
+    ctx.update_T_prepare(Wg, H2, nbits)
+    Tnew = ctx.update_T(Wg, H2, Q, T0.clone(), nbits)
+    ctx.update_T_prepare(None, None, nbits)
+    Tfresh = ctx.update_T(Wg, H2, Q, T0.clone(), nbits)
+    assert torch.equal(Tnew, Tfresh) and not torch.equal(Tnew, Told)
+    Tref, _ = ref.update_T(W.numpy().astype(np.float64), H2.cpu().numpy().astype(np.float64), Q.cpu().numpy(), nbits)
+    err = np.abs(Tnew.cpu().numpy() - Tref).max(axis=1) / np.abs(Tref).max(axis=1)
+    assert err.max() <= 1e-4
+
+
 def _structured_H(kind, n, seed):
     """Second-moment matrices that drive the integer representation of H in the T-update through
     its cases: weakly or strongly correlated features (two or three digits per entry), feature
