@@ -38,8 +38,13 @@ def layer():
     ctx.close()
 
 
-def h_tol(p):
-    return max(2e-6, 5.0 * 2.0 ** -24 * np.sqrt(p / 3.0))
+def h_tol(p, heavy=False):
+    """|dH_jk| / sqrt(H_jj H_kk): the fp32 sums of the product kernel run over at most p / 16 tokens per
+    partial and the partials are added pairwise, so the error grows far more slowly than a running sum's
+    eps sqrt(p / 3); the factor is set about ten times above what the workloads measure (5e-7 on
+    Gaussian activations at p = 262144, 4e-6 on the heavy-tailed ones at p = 131072, whose fp16 values
+    reach 475 and cancel in the sums)."""
+    return max(2e-6, (2.5 if heavy else 0.35) * 2.0 ** -24 * np.sqrt(p / 3.0))
 
 
 def test_full_hessian_sampled_entries(layer):
@@ -97,7 +102,7 @@ def test_full_solver_on_sampled_rows(layer):
           % (ROWS, float((gap == 0).mean()), int(((gap > 0) & (rel < NEAR_TIE)).sum()), viol,
              float((Qs == Qref).mean()), float((Qs == Qref).all(axis=1).mean())))
     assert viol == 0
-    assert float((Qs == Qref).mean()) >= 0.98
+    assert float((Qs == Qref).mean()) >= 0.9995
 
     # one T-update on the GPU's Q
     T1 = ctx.update_T(Wf, H, Q, T0.clone(), nbits)
@@ -105,6 +110,23 @@ def test_full_solver_on_sampled_rows(layer):
     err = np.abs(T1[torch.from_numpy(rows).cuda()].cpu().numpy() - T1ref).max(axis=1) / np.abs(T1ref).max(axis=1)
     print("full-size T-update: max row error %.2e" % err.max())
     assert err.max() <= 1e-4
+    # The sums of Eq. (7) run on 16-bit integer digits of H and G = W H on two-piece fp16 splits:
+    # that must be no worse than evaluating the same formula plainly in float32 (one-hot products,
+    # float32 accumulation, float32 solve) on the same rows.
+    H32 = H.cpu().numpy()
+    C = 1 << nbits
+    err32 = np.zeros(len(rows))
+    for r in range(len(rows)):
+        S = np.zeros((C, cfg.n), dtype=np.float32)
+        S[Qs[r].astype(np.int64), np.arange(cfg.n)] = 1.0
+        SH = S @ H32
+        A32 = SH @ S.T
+        b32 = (Ws[r].astype(np.float32) @ H32) @ S.T
+        t32 = np.linalg.solve(A32, b32)
+        err32[r] = np.abs(t32.astype(np.float64) - T1ref[r]).max() / np.abs(T1ref[r]).max()
+    print("the same T-update evaluated in plain float32: max row error %.2e, median %.2e (GPU median %.2e)"
+          % (err32.max(), np.median(err32), np.median(err)))
+    assert err.max() <= max(err32.max(), 2e-6) and np.median(err) <= max(np.median(err32), 1e-6)
 
     # loss of (T1, Q)
     loss, rl = ctx.layer_loss(Wf, H, T1, Q, nbits, want_rows=True)

@@ -30,8 +30,13 @@ pytestmark = pytest.mark.gpu
 NEAR_TIE = 1e-6
 
 
-def h_tol(p):
-    return max(2e-6, 5.0 * 2.0 ** -24 * np.sqrt(p / 3.0))
+def h_tol(p, heavy=False):
+    """|dH_jk| / sqrt(H_jj H_kk): the fp32 sums of the product kernel run over at most p / 16 tokens per
+    partial and the partials are added pairwise, so the error grows far more slowly than a running sum's
+    eps sqrt(p / 3); the factor is set about ten times above what the workloads measure (5e-7 on
+    Gaussian activations at p = 262144, 4e-6 on the heavy-tailed ones at p = 131072, whose fp16 values
+    reach 475 and cancel in the sums)."""
+    return max(2e-6, (2.5 if heavy else 0.35) * 2.0 ** -24 * np.sqrt(p / 3.0))
 
 
 def run_layer(name, rows_s, rows_t, bit_widths=None, free_rows=4):
@@ -57,8 +62,9 @@ def run_layer(name, rows_s, rows_t, bit_widths=None, free_rows=4):
         Hs = H[it][:, it].cpu().numpy().astype(np.float64)
         d = np.sqrt(np.diag(Href))
         rel = float((np.abs(Hs - Href) / np.outer(d, d)).max())
-        print("%s H: max |dH|/sqrt(HjjHkk) = %.2e (tol %.2e)" % (name, rel, h_tol(cfg.p)))
-        assert rel <= h_tol(cfg.p)
+        heavy = cfg.x_kind == "heavy"
+        print("%s H: max |dH|/sqrt(HjjHkk) = %.2e (tol %.2e)" % (name, rel, h_tol(cfg.p, heavy)))
+        assert rel <= h_tol(cfg.p, heavy)
         del X, Xs
         torch.cuda.empty_cache()
         H64 = H.cpu().numpy().astype(np.float64)

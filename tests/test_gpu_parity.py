@@ -4,7 +4,7 @@ inputs), plus the degenerate cases.  Sizes span several tiles and a ragged tail
 while staying small enough for the oracle to finish in seconds.
 
 Tolerances (derived from the arithmetic of the kernels):
-  H        |dH_jk| <= h_tol(p) sqrt(H_jj H_kk), h_tol = max(2e-6, 5 eps sqrt(p/3)): fp32 running
+  H        |dH_jk| <= h_tol(p) sqrt(H_jj H_kk), h_tol = max(2e-6, 0.35 eps sqrt(p/3)) (2.5 for heavy tails): fp32
            sums of p products (sequential accumulation error, 4.5 sigma over n^2 entries)
   L        |L L^T - H|_F <= 2e-6 |H|_F, |L - L_ref|_F <= 1e-4 |L_ref|_F
   T^0      1 ulp of fp32
@@ -50,15 +50,22 @@ def make_problem(m, n, p, nbits, seed=0, x_dtype=torch.float16, w_kind="student_
     return W, X
 
 
-def h_tol(p):
-    return max(2e-6, 5.0 * 2.0 ** -24 * np.sqrt(p / 3.0))
+def h_tol(p, heavy=False):
+    """|dH_jk| / sqrt(H_jj H_kk): the fp32 sums of the product kernel run over at most p / 16 tokens per
+    partial and the partials are added pairwise, so the error grows far more slowly than a running sum's
+    eps sqrt(p / 3); the factor is set about ten times above what the workloads measure (5e-7 on
+    Gaussian activations at p = 262144, 4e-6 on the heavy-tailed ones at p = 131072, whose fp16 values
+    reach 475 and cancel in the sums)."""
+    return max(2e-6, (2.5 if heavy else 0.35) * 2.0 ** -24 * np.sqrt(p / 3.0))
 
 
-def check_H(H, Href, p, label=""):
+def check_H(H, Href, p, label="", wide=False):
+    """wide: fp32 activations (their products are rounded, fp16 products are exact in fp32) or
+    heavy-tailed ones."""
     d = np.sqrt(np.diag(Href))
     rel = np.abs(H - Href) / (np.outer(d, d) + 1e-300)
-    print("%s H: max |dH|/sqrt(HjjHkk) = %.2e (tol %.2e)" % (label, rel.max(), h_tol(p)))
-    assert rel.max() <= h_tol(p)
+    print("%s H: max |dH|/sqrt(HjjHkk) = %.2e (tol %.2e)" % (label, rel.max(), h_tol(p, wide)))
+    assert rel.max() <= h_tol(p, wide)
 
 
 def check_S(W64, L64, T64, Q_gpu, label=""):
@@ -173,7 +180,9 @@ def test_cholesky_preconditioning_modes(ctx):
         Hp = ref.precondition(H64, omode, lam)
         Lref, _ = ref.cholesky(H64, omode, lam)
         assert np.linalg.norm(L @ L.T - Hp) <= 2e-6 * np.linalg.norm(Hp)
-        assert np.linalg.norm(L - Lref) <= 1e-3 * np.linalg.norm(Lref)
+        rl = np.linalg.norm(L - Lref) / np.linalg.norm(Lref)
+        print("preconditioned factor, mode %d: |L - Lref| / |Lref| = %.2e" % (mode, rl))
+        assert rl <= 5e-6
 
 
 def test_cholesky_numerically_singular_is_reported(ctx):
@@ -248,7 +257,7 @@ def test_update_S_stagewise(ctx, m, n, nbits):
     agree = float((Q == Qref).mean())
     rows_same = float((Q == Qref).all(axis=1).mean())
     print("free-running agreement: indices %.6f, rows %.4f" % (agree, rows_same))
-    assert agree >= 0.98
+    assert agree >= 0.999
 
 
 def test_update_S_ties_and_identity(ctx):
@@ -472,7 +481,7 @@ def test_quantize_layer_config1(ctx):
     Wg, Xg = W.cuda(), X.cuda()
     H = ctx.build_hessian(Xg)
     Href = ref.build_hessian(X.numpy())
-    check_H(H.cpu().numpy().astype(np.float64), Href, cfg.p, "c1")
+    check_H(H.cpu().numpy().astype(np.float64), Href, cfg.p, "c1", wide=True)      # fp32 activations
     L, info = ctx.cholesky(H)
     assert info == 0
     K = cfg.iters
@@ -623,7 +632,9 @@ def test_quantize_layer_rank_deficient_activations(ctx, mode):
     Lref, _ = ref.cholesky(H64, omode, lam)
     Lg, info = ctx.cholesky(H, gmode, lam)
     assert info == 0
-    assert np.linalg.norm(Lg.cpu().numpy() - Lref) <= 1e-3 * np.linalg.norm(Lref)
+    rl = np.linalg.norm(Lg.cpu().numpy() - Lref) / np.linalg.norm(Lref)
+    print("rank-deficient %s: |L - Lref| / |Lref| = %.2e" % (mode, rl))
+    assert rl <= 1e-4
     L64 = Lg.cpu().numpy().astype(np.float64)
     _, _, viol = check_S(W64, L64, Tprev.cpu().numpy().astype(np.float64), Q.cpu().numpy(), "rank-deficient " + mode)
     assert viol == 0
@@ -810,5 +821,6 @@ def test_pipeline_shape_sweep(ctx, m, n, nbits, seed):
     assert np.all(np.abs(T2.cpu().numpy() - Tref).max(axis=1) / scale <= 1e-4)
     lref = ref.layer_loss(W64, H64, T2.cpu().numpy(), Q2.cpu().numpy())[0]
     base = float(((W64 @ H64) * W64).sum())          # ||W X||^2: the scale of fp32 noise when the fit is exact
-    assert abs(hist[-1] - lref) <= 1e-4 * lref + 1e-6 * base
-    assert hist[3] <= hist[2] * (1 + 1e-5) + 1e-6 * base
+    # (2e-7 of ||W X||^2 is the fp32 floor of the loss product when the fit is exact and lref is ~0)
+    assert abs(hist[-1] - lref) <= 1e-4 * lref + 2e-7 * base
+    assert hist[3] <= hist[2] * (1 + 1e-5) + 2e-7 * base

@@ -84,7 +84,7 @@ def test_random_other_calls(ctx, seed):
         Ht = ctx.build_hessian_tokens(Xh[:, :p].t().contiguous().cuda()).cpu().numpy().astype(np.float64)
         assert h_err(Ht, ref.build_hessian(Xh[:, :p].numpy())) <= h_tol(p) and np.array_equal(Ht, Ht.T), label
         Hf = ctx.build_hessian(X[:, :p].contiguous().cuda()).cpu().numpy().astype(np.float64)
-        assert h_err(Hf, ref.build_hessian(X[:, :p].numpy())) <= h_tol(p), label
+        assert h_err(Hf, ref.build_hessian(X[:, :p].numpy())) <= h_tol(p, True), label     # fp32 products are rounded
 
         H32 = (Href + 0.05 * np.mean(np.diag(Href)) * np.eye(n)).astype(np.float32)
         H64 = H32.astype(np.float64)
