@@ -32,6 +32,8 @@
 //            equal codes resolve to the lower index.
 // The slab's residuals E live in scratch in a (column, row-in-slab) layout so
 // that one MFMA operand fetch is 64 consecutive floats.
+#include <cstdlib>
+
 #include "ganq_internal.h"
 
 namespace ganq {
@@ -413,10 +415,270 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
   }
 }
 
+
+// ---- 32 rows per workgroup ----
+// The same sweep with a slab of 32 rows: every compute unit still streams all of tril(L), but for
+// twice the rows, which halves the L2 -> CU traffic per row where it is the limit (wide layers with
+// enough rows to fill the chip with 32-row slabs).  Phase 1 uses v_mfma_f32_32x32x2_f32: lane l
+// supplies E[row l % 32][k = l / 32] and, as one 8-byte load, L[k][2 (l % 32) + t] for the two
+// column tiles t = 0, 1 (tile t, lane column c holds block column 2 c + t).  All eight wavefronts
+// have rows in phase 2 (4 each), so there is no early stretch of the next far part; the first
+// fragments of the next far part are still requested before phase 2.
+struct LFrag32 {
+  float a;
+  float2 b;
+};
+constexpr int SR32 = 32;
+constexpr int RED32_FLOATS = NW * 2 * 16 * 64;                    // partial accumulators of phase 1
+constexpr int S32_LDS_BYTES = (SB * (SB + 4) + RED32_FLOATS) * (int)sizeof(float);
+
+template <bool VECL>
+__global__ __launch_bounds__(64 * NW) void update_S32_kernel(const float* __restrict__ W, int64_t m,
+                                                         int64_t n, int64_t ldw,
+                                                         const float* __restrict__ L, int64_t ldl,
+                                                         const float* __restrict__ rdiag,
+                                                         const float* __restrict__ T, int C,
+                                                         uint8_t* __restrict__ Q, int64_t ldq,
+                                                         float* __restrict__ E, int64_t lde,
+                                                         float* __restrict__ Es) {
+  extern __shared__ __attribute__((aligned(16))) float s32mem[];
+  float (*Ld)[SB + 4] = reinterpret_cast<float (*)[SB + 4]>(s32mem);       // diagonal block of L
+  float* red = s32mem + SB * (SB + 4);                                      // [wave][t][v][lane]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int r = 4 * wave + g;                       // row within the slab (phase 2)
+  const int64_t row0 = (int64_t)blockIdx.x * SR32;
+  const int64_t row = row0 + r;
+  const bool row_ok = row < m;
+  float* __restrict__ Eslab = Es + (int64_t)blockIdx.x * n * SR32;
+
+  // ---- sort this row's codebook (stable), build midpoints and tie representatives ----
+  float tc = __builtin_huge_valf();
+  if (c < C) tc = row_ok ? T[row * C + c] : 0.f;
+  int rank = 0;
+  RankLoop<15>::run(tc, c, rank);
+  const int paddr = ((lane & 48) | rank) << 2;
+  const float ts = __builtin_bit_cast(float, __builtin_amdgcn_ds_permute(paddr, __builtin_bit_cast(int, tc)));
+  const int orig = __builtin_amdgcn_ds_permute(paddr, c);
+  int rep = orig;
+  RepLoop<15>::run(ts, orig, rep);
+  const float tnext = dpp_f<0x101>(ts);             // row_shl:1 -> value of lane c + 1
+  const float mid = (c < 15) ? 0.5f * (ts + tnext) : __builtin_huge_valf();
+  const int gshift = 16 * g;
+
+  // Far part of the block that starts at column jb over the rows k in [ks, n): this wavefront takes
+  // the k-pairs wv, wv + NW, ...; iteration it covers rows ks + 2 wv + 2 NW it + (lane / 32), walked
+  // from the last iteration (oldest columns) down to 0.  Rows k >= n fall outside the descriptors
+  // and read as zero.
+  struct Far {
+    __amdgpu_buffer_rsrc_t rl, re;
+    uint32_t nch;
+    uint32_t lstep, estep;
+    bool active;
+  };
+  const int wv = __builtin_amdgcn_readfirstlane(wave);
+  const int c32 = lane & 31, kk = lane >> 5;
+  const uint32_t loff = (uint32_t)((kk * ldl + 2 * c32) * sizeof(float));
+  const uint32_t eoff = (uint32_t)((kk * SR32 + c32) * sizeof(float));
+  auto far_setup = [&](int64_t jb, int64_t ks) {
+    Far F;
+    const int64_t krow = ks + 2 * wv;
+    F.active = krow < n;
+    F.nch = 0;
+    F.lstep = (uint32_t)(2 * NW * ldl * sizeof(float));
+    F.estep = (uint32_t)(2 * NW * SR32 * sizeof(float));
+    const int64_t kr = F.active ? krow : 0;
+    const int64_t lbytes = F.active ? ((n - 1 - kr) * ldl + n - jb) * (int64_t)sizeof(float) : 0;
+    const int64_t ebytes = F.active ? (n - kr) * SR32 * (int64_t)sizeof(float) : 0;
+    F.rl = __builtin_amdgcn_make_buffer_rsrc((void*)(L + kr * ldl + jb), 0, (int)lbytes, 0x00020000);
+    F.re = __builtin_amdgcn_make_buffer_rsrc((void*)(Eslab + kr * SR32), 0, (int)ebytes, 0x00020000);
+    if (F.active) {
+      const uint32_t niter = (uint32_t)ceil_div(n - krow, 2 * NW);
+      F.nch = (niter + PU - 1) / PU;
+    }
+    return F;
+  };
+  auto far_fetch = [&](const Far& F, uint32_t it) {
+    const uint32_t rr = F.nch * PU - 1 - it;
+    LFrag32 f;
+    f.a = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.re, eoff, rr * F.estep, 0));
+    if (VECL) {
+      f.b = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(F.rl, loff, rr * F.lstep, 0));
+    } else {
+      f.b.x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff, rr * F.lstep, 0));
+      f.b.y = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(F.rl, loff + 4, rr * F.lstep, 0));
+    }
+    return f;
+  };
+  LFrag32 fa[PU], fb[PU];
+  bool prefetched = false;
+  auto far_run = [&](const Far& F, floatx16 (&macc)[2], bool have_first) {
+    if (!F.active) return;
+    auto mma = [&](const LFrag32& f) {
+      macc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a, f.b.x, macc[0], 0, 0, 0);
+      macc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a, f.b.y, macc[1], 0, 0, 0);
+    };
+    if (!have_first) {
+#pragma unroll
+      for (int u = 0; u < PU; ++u) fa[u] = far_fetch(F, u);
+    }
+    bool in_a = true;
+    for (uint32_t ch = 0; ch + 1 < F.nch; ++ch) {
+      if (in_a) {
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+          fb[u] = far_fetch(F, (ch + 1) * PU + u);
+          __builtin_amdgcn_sched_barrier(0);
+          mma(fa[u]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < PU; ++u) {
+          fa[u] = far_fetch(F, (ch + 1) * PU + u);
+          __builtin_amdgcn_sched_barrier(0);
+          mma(fb[u]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      in_a = !in_a;
+    }
+    if (in_a) {
+#pragma unroll
+      for (int u = 0; u < PU; ++u) mma(fa[u]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < PU; ++u) mma(fb[u]);
+    }
+  };
+
+  const bool vec4 = (ldl % 4 == 0) && ((((uintptr_t)L) & 15) == 0);
+  const int nblk = (int)ceil_div(n, SB);
+  for (int b = nblk - 1; b >= 0; --b) {
+    const int64_t j0 = (int64_t)b * SB;
+    const int bw = (int)((n - j0 < SB) ? n - j0 : SB);
+    const int64_t kstart = j0 + SB;
+
+    // ---- fetch the diagonal block of L (written to LDS after phase 1) and this block's W ----
+    constexpr int STG = SB * SB / 4 / (64 * NW);     // float4 units per thread
+    float stg[STG][4];
+#pragma unroll
+    for (int u = 0; u < STG; ++u) {
+      const int e4 = tid + u * 64 * NW;
+      const int rr = e4 / (SB / 4), cc = (e4 % (SB / 4)) * 4;
+      const int64_t gr = j0 + rr, gc = j0 + cc;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) stg[u][i] = 0.f;
+      if (gr < n && cc < rr) {
+        if (vec4 && gc + 3 < n) {
+          const float4 q4 = *reinterpret_cast<const float4*>(L + gr * ldl + gc);
+          stg[u][0] = q4.x; stg[u][1] = q4.y; stg[u][2] = q4.z; stg[u][3] = q4.w;
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) stg[u][i] = (gc + i < n) ? L[gr * ldl + gc + i] : 0.f;
+        }
+      }
+    }
+    float Wr[4], rd[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int64_t col = j0 + 16 * q + c;
+      Wr[q] = (row_ok && col < n) ? W[row * ldw + col] : 0.f;
+      rd[q] = (col < n) ? rdiag[col] : 0.f;
+    }
+
+    // ---- phase 1: acc = E[:, kstart:] * L[kstart:, block] on the matrix cores ----
+    floatx16 macc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) macc[t][v] = 0.f;
+    {
+      const Far F = far_setup(j0, kstart);
+      far_run(F, macc, prefetched);
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) red[((wave * 2 + t) * 16 + v) * 64 + lane] = macc[t][v];
+#pragma unroll
+    for (int u = 0; u < STG; ++u) {
+      const int e4 = tid + u * 64 * NW;
+      const int rr = e4 / (SB / 4), cc = (e4 % (SB / 4)) * 4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) Ld[rr][cc + i] = (cc + i < rr) ? stg[u][i] : 0.f;
+    }
+    // the first fragments of the next block's far part (its oldest rows) do not depend on this
+    // block's decisions: they are requested now and arrive while the sequential phase runs
+    prefetched = false;
+    if (b > 0) {
+      const Far Fn = far_setup(j0 - SB, j0);
+      if (Fn.active && Fn.nch >= 2) {
+#pragma unroll
+        for (int u = 0; u < PU; ++u) fa[u] = far_fetch(Fn, u);
+        prefetched = true;
+      }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+
+    {
+      // tile t, lane l', register v hold (row 8 (v / 4) + 4 (l' / 32) + v % 4, block column 2 (l' % 32) + t)
+      float acc[4];
+      const int vv = ((r >> 3) << 2) | (r & 3), khp = (r >> 2) & 1;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int jl = 16 * q + c;
+        const int t = jl & 1, sl = (jl >> 1) + 32 * khp;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sum += red[((w * 2 + t) * 16 + vv) * 64 + sl];
+        acc[q] = sum;
+      }
+
+      // ---- phase 2: the block's columns, right to left ----
+      float Er[4] = {0.f, 0.f, 0.f, 0.f};
+      int Ir[4] = {0, 0, 0, 0};
+      float l0[4], l1[4];
+      load_lrow<SB - 1>(Ld, c, l0);
+      load_lrow<SB - 2>(Ld, c, l1);
+      if (bw == SB)
+        Step<SB - 1, true>::run(bw, c, gshift, ts, mid, Wr, rd, acc, Er, Ir, Ld, l0, l1);
+      else
+        Step<SB - 1, false>::run(bw, c, gshift, ts, mid, Wr, rd, acc, Er, Ir, Ld, l0, l1);
+
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int64_t col = j0 + 16 * q + c;
+        const int qi = __shfl(rep, (lane & 48) | Ir[q], 64);     // sorted position -> original index
+        if (col < n) {
+          Eslab[col * SR32 + r] = Er[q];
+          if (row_ok) {
+            Q[row * ldq + col] = (uint8_t)qi;
+            if (E != nullptr) E[row * lde + col] = Er[q];
+          }
+        }
+      }
+    }
+    __syncthreads();   // E of this block visible to all wavefronts; LDS reusable
+  }
+}
+
+// Rows per workgroup for this shape: 32 where 32-row slabs still give every compute unit one, and
+// the layer is wide enough for the stream of L to matter; GANQ_S_SLAB_ROWS = 16 / 32 in the
+// environment overrides the choice (used by the tests to reach both kernels at any size).
+int slab_rows_for(int64_t m, int64_t n) {
+  const char* f = getenv("GANQ_S_SLAB_ROWS");
+  if (f != nullptr && f[0] == '3' && f[1] == '2' && f[2] == 0) return 32;
+  if (f != nullptr && f[0] == '1' && f[1] == '6' && f[2] == 0) return 16;
+  return (ceil_div(m, 32) >= 240 && n >= 8192) ? 32 : 16;
+}
+
 }  // namespace
 
 size_t update_s_scratch_bytes(int64_t m, int64_t n) {
-  return align_up((size_t)pad_rows(m) * (size_t)n * sizeof(float)) + align_up((size_t)n * sizeof(float));
+  const int64_t mp = ceil_div(m, 32) * 32;      // either slab height
+  return align_up((size_t)mp * (size_t)n * sizeof(float)) + align_up((size_t)n * sizeof(float));
 }
 
 hipError_t launch_update_S(hipStream_t s, const float* W, int64_t m, int64_t n, int64_t ldw,
@@ -424,10 +686,24 @@ hipError_t launch_update_S(hipStream_t s, const float* W, int64_t m, int64_t n, 
                            int64_t ldq, float* E, int64_t lde, void* scratch) {
   const int vecL = (ldl % 4 == 0) && (((uintptr_t)L) % 16 == 0);
   float* Es = (float*)scratch;
-  float* rdiag = (float*)((char*)scratch + align_up((size_t)pad_rows(m) * (size_t)n * sizeof(float)));
+  float* rdiag = (float*)((char*)scratch + align_up((size_t)(ceil_div(m, 32) * 32) * (size_t)n * sizeof(float)));
   hipLaunchKernelGGL(rdiag_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, L, n, ldl, rdiag);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (slab_rows_for(m, n) == 32) {
+    static std::atomic<uint64_t> lds_a{0}, lds_b{0};
+    const int vec2 = (ldl % 2 == 0) && (((uintptr_t)L) % 8 == 0);
+    if (vec2) {
+      if ((e = ensure_dynamic_lds((const void*)update_S32_kernel<true>, S32_LDS_BYTES, lds_a)) != hipSuccess) return e;
+      hipLaunchKernelGGL(update_S32_kernel<true>, dim3((unsigned)ceil_div(m, SR32)), dim3(64 * NW), S32_LDS_BYTES, s,
+                         W, m, n, ldw, L, ldl, rdiag, T, 1 << nbits, Q, ldq, E, lde, Es);
+    } else {
+      if ((e = ensure_dynamic_lds((const void*)update_S32_kernel<false>, S32_LDS_BYTES, lds_b)) != hipSuccess) return e;
+      hipLaunchKernelGGL(update_S32_kernel<false>, dim3((unsigned)ceil_div(m, SR32)), dim3(64 * NW), S32_LDS_BYTES, s,
+                         W, m, n, ldw, L, ldl, rdiag, T, 1 << nbits, Q, ldq, E, lde, Es);
+    }
+    return hipGetLastError();
+  }
   if (vecL)
     hipLaunchKernelGGL(update_S_kernel<true>, dim3((unsigned)ceil_div(m, SR)), dim3(64 * NW), 0, s, W,
                        m, n, ldw, L, ldl, rdiag, T, 1 << nbits, Q, ldq, E, lde, Es);

@@ -260,6 +260,38 @@ def test_update_S_stagewise(ctx, m, n, nbits):
     assert agree >= 0.999
 
 
+@pytest.mark.parametrize("m,n,nbits", [(40, 200, 4), (33, 65, 4), (1, 1, 2), (7, 130, 1), (70, 1000, 3), (64, 777, 4)])
+def test_update_S_32_row_slabs(ctx, m, n, nbits, monkeypatch):
+    """The 32-row kernel of the S-update (chosen by the library for wide layers with many rows), forced
+    here at small sizes: every choice is optimal for its float64 target, the residual output is exact,
+    strided operands work, and it agrees with the 16-row kernel up to near ties."""
+    W, X = make_problem(m, n, max(4 * n, 64), nbits)
+    H64 = ref.build_hessian(X.numpy())
+    L32 = torch.from_numpy(ref.cholesky(H64)[0]).float()
+    T32 = torch.from_numpy(ref.init_codebooks(W.numpy(), nbits)).float()
+    monkeypatch.setenv("GANQ_S_SLAB_ROWS", "16")
+    Q16 = ctx.update_S(W.cuda(), L32.cuda(), T32.cuda(), nbits).cpu().numpy()
+    monkeypatch.setenv("GANQ_S_SLAB_ROWS", "32")
+    Q, E = ctx.update_S(W.cuda(), L32.cuda(), T32.cuda(), nbits, want_E=True)
+    # odd leading dimension of L (no 8-byte loads) and of W
+    Lw = torch.zeros(n, n + 3, device="cuda")
+    Lw[:, :n] = L32.cuda()
+    Ww = torch.zeros(m, n + 5, device="cuda")
+    Ww[:, :n] = W.cuda()
+    Qs = ctx.update_S(Ww[:, :n], Lw[:, :n], T32.cuda(), nbits).cpu().numpy()
+    monkeypatch.delenv("GANQ_S_SLAB_ROWS")
+    Q = Q.cpu().numpy()
+    E = E.cpu().numpy()
+    W64, L64, T64 = W.numpy().astype(np.float64), L32.numpy().astype(np.float64), T32.numpy().astype(np.float64)
+    assert Q.max() < (1 << nbits)
+    assert np.array_equal(E, W.numpy() - np.take_along_axis(T32.numpy(), Q.astype(np.int64), axis=1))
+    _, _, viol = check_S(W64, L64, T64, Q, "S32 %dx%d N=%d" % (m, n, nbits))
+    assert viol == 0
+    _, _, viol = check_S(W64, L64, T64, Qs, "S32 strided %dx%d N=%d" % (m, n, nbits))
+    assert viol == 0
+    assert float((Q == Q16).mean()) >= 0.999 and float((Qs == Q16).mean()) >= 0.999
+
+
 def test_update_S_ties_and_identity(ctx):
     # H = I: plain nearest rounding; duplicated codebook entries: lowest index wins
     T = np.array([[0.0, 1.0, 1.0, 0.0], [-1.0, -1.0, 2.0, 2.0]], dtype=np.float32)
