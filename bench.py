@@ -93,8 +93,12 @@ def kernel_work(cls, m, n, p, nbits, iters):
         return "mfma", 2.0 * m * n * n, "TFLOP/s", PEAK_F16_TFLOPS
     if cls == "update_s":
         return "mfma", float(m) * n * n, "TFLOP/s", PEAK_F32_MFMA_TFLOPS      # triangular: m n^2 / 2 MACs
-    if cls in ("t_accum", "t_delta"):
+    if cls == "t_accum":
         return "alu", 0.5 * m * n * n, "TFLOP/s", PEAK_F32_ADD_TOPS           # m n^2 / 2 additions
+    if cls == "t_delta":
+        # gather of the rows of H that belong to the changed columns: two digit bytes per entry; the
+        # number of changed columns comes from the library's sweep log (filled in by main())
+        return "hbm", 0.0, "GB/s", PEAK_HBM_GBS
     if cls == "loss":
         return "mfma", 2.0 * m * n * n, "TFLOP/s", PEAK_F16_TFLOPS
     if cls == "t_prep":
@@ -239,6 +243,53 @@ def decode_main(args):
     print(json.dumps(out))
 
 
+def stacked_main(args):
+    """Layers that see the same activations (q/k/v, gate/up) share H and its factor, and rows are
+    independent (Section 3.1): their weights stacked row-wise go through ONE ganq_quantize_layer call.
+    Times three 4096 x 4096 layers (config c3's recipe, three seeds) solved by three calls against one
+    stacked call, H given and factored inside each call as the benchmark step does."""
+    import torch
+    from paper_2501_12956_amd import binding, synth
+
+    cfg = synth.CONFIGS[args.config]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    Ws = [synth.make_weight(cfg, sd, dev) for sd in (0, 1, 2)]
+    X = synth.make_activations(cfg, 0, dev)
+    ctx = binding.Context(0)
+    ctx.reserve(3 * cfg.m, cfg.n, cfg.p, cfg.nbits)
+    H = ctx.build_hessian(X)
+    del X
+    Wall = torch.cat(Ws, 0).contiguous()
+
+    def three():
+        return [ctx.quantize_layer(W, H, cfg.nbits, cfg.iters) for W in Ws]
+
+    def one():
+        return ctx.quantize_layer(Wall, H, cfg.nbits, cfg.iters)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            out = fn()
+        torch.cuda.synchronize()
+        return 1e3 * (time.perf_counter() - t0) / args.steps, out
+
+    t3, outs = timed(three)
+    t1, (Tall, Qall) = timed(one)
+    # rows are independent: the stacked call reproduces the separate calls up to near ties
+    same = [float((Qall[k * cfg.m:(k + 1) * cfg.m] == outs[k][1]).all(dim=1).float().mean()) for k in range(3)]
+    print(json.dumps({
+        "metric": "ms for three %dx%d layers sharing H (%d-bit, %d iters): three calls vs one stacked call"
+                  % (cfg.m, cfg.n, cfg.nbits, cfg.iters),
+        "three_calls_ms": t3, "stacked_call_ms": t1, "ratio": t3 / t1, "steps": args.steps, "warmup": args.warmup,
+        "identical_rows_fraction": same, "n_gpus": 1, "data": "synthetic",
+        "config": {"workload": "%s recipe, seeds 0-2 for W, one X" % cfg.name}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -254,6 +305,8 @@ def main():
     ap.add_argument("--decode", action="store_true",
                     help="time the deployment-side look-up-table product instead of the solver")
     ap.add_argument("--nbits", type=int, default=4, help="--decode only: bits per stored code")
+    ap.add_argument("--stacked", action="store_true",
+                    help="time three layers that share their activations: three calls against one stacked call")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the solver has no multi-GPU path); "
@@ -262,6 +315,8 @@ def main():
 
     if args.decode:
         return decode_main(args)
+    if args.stacked:
+        return stacked_main(args)
 
     import torch
     from paper_2501_12956_amd import binding, synth
@@ -320,14 +375,19 @@ def main():
             return peaks["f16_mfma_tflops"]
         if cls in ("t_accum", "t_delta"):
             # additions that run as int8 one-hot products: 2 C digits operations issued per addition
-            return peaks["i8_mfma_tops"] / (2.0 * (1 << cfg.nbits) * 2)
+            return peaks["i8_mfma_tops"] / (2.0 * (1 << cfg.nbits) * 2) if cls == "t_accum" else peaks["copy_gbs"]
         return peaks["f32_mfma_tflops"]
 
+    log = ctx.sweep_log()
+    upd = [t for (u, _, t) in log if u]
+    npad = (n + 127) // 128 * 128
     kernels = {}
     for cls, (ms, cnt) in prof.items():
         if cnt == 0:
             continue
         bound, work, unit, peak = kernel_work(cls, m, n, p, cfg.nbits, cfg.iters)
+        if cls == "t_delta" and upd:
+            work = 2.0 * npad * sum(upd) / len(upd)      # bytes gathered per updating sweep (served by L2 / MALL)
         avg_ms = ms / cnt
         rate = work / (avg_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9) if avg_ms > 0 else 0.0
         mp = measured_peak(cls, unit, bound)
@@ -373,6 +433,9 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
         "measured_peaks": peaks or None,
+        # per sweep of the last step: did it update S_i H S_i^T from the changed columns (1) or sum it
+        # again (0); the most changed indices in a row; their total
+        "sweeps": log,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, X, W)
