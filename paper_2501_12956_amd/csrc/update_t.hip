@@ -454,11 +454,15 @@ __device__ inline int4v onehot16(uint4 q, uint32_t brep, uint4 cs) {
 //   A[a, b] += sum_j d_j[a] w_j Znew[j, b] + sum_j d_j[b] w_j Zold[j, a]
 // is accumulated per lane in float64 (a lane owns one column of Z, i.e. one b or one a) and written
 // to the chunk's slot of Dpart; the solve kernel adds a row's slots to its state in a fixed order.
-// The kernel is bound by the latency of the gathered loads, so it is kept small enough in registers
-// for four wavefronts per SIMD.
-constexpr int DB = 4;           // k-steps fetched together: one 128-byte line per gathered row and digit
+// The kernel is bound by the gathered loads.  They are issued as whole 128-byte lines (8 lanes per
+// row, 8 rows per instruction) - a request per row and k-step in the operand layout (2 lanes per
+// row) costs the cache four look-ups per line - and turned into the operand layout through a
+// wavefront-private piece of LDS (rows padded to 144 bytes: conflict-free 16-byte reads of 16
+// consecutive rows); the next batch's lines are requested before the current batch is multiplied.
+constexpr int DROWB = 144;                       // LDS bytes per staged row
+constexpr int DSTAGE = 2 * 32 * DROWB;           // per wavefront: two digits x 32 rows
 template <int NBITS>
-__global__ __launch_bounds__(256, 4) void t_delta_kernel(const int8_t* __restrict__ Hs, int64_t npad,
+__global__ __launch_bounds__(256, 3) void t_delta_kernel(const int8_t* __restrict__ Hs, int64_t npad,
                                                          const uint8_t* __restrict__ Qnew,
                                                          const uint8_t* __restrict__ Qold,
                                                          const uint8_t* __restrict__ Cs,
@@ -470,7 +474,7 @@ __global__ __launch_bounds__(256, 4) void t_delta_kernel(const int8_t* __restric
                                                          int64_t m, int64_t n,
                                                          double* __restrict__ Dpart) {
   constexpr int C = 1 << NBITS;
-  __shared__ double Rs[4][64][C + 1];
+  __shared__ __attribute__((aligned(16))) unsigned char dsm[4][DSTAGE];
   if (!t_use_delta(Tstat, m, n, fmax)) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -491,32 +495,59 @@ __global__ __launch_bounds__(256, 4) void t_delta_kernel(const int8_t* __restric
   const uint8_t* __restrict__ csrow = Cs + 16 * kh;
   const int64_t ps = npad * npad;
 
+  // lane c (and c + 32) holds entry c of the chunk: changed column, old and new code, row factor
   const int e0 = t0 + c;
   const uint32_t ent = (e0 < cnt) ? Flist[i * fmax + e0] : 0u;
   const int64_t jrow = ent & 0xffffu;
-  const float wrow = (e0 < cnt) ? Wj[jrow] : 0.f;       // rows beyond the count add nothing
-  const int8_t* __restrict__ hrow = Hs + jrow * npad + 16 * kh;
+  const float wrow = (e0 < cnt) ? Wj[jrow] : 0.f;       // entries beyond the count add nothing
+  // gather side: instruction t fetches rows 8 t + lane / 8, 16-byte piece lane % 8 of the line
+  const int gr = lane >> 3, gp = lane & 7;
+  const int8_t* __restrict__ grow[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int64_t jt = __shfl((int)jrow, 8 * t + gr, 64);
+    grow[t] = Hs + jt * npad + 16 * gp;
+  }
+  unsigned char* __restrict__ stage = dsm[wave];
+  const int wr_off = gr * DROWB + gp * 16;               // + (8 t) * DROWB + digit * 32 * DROWB
+  const int rd_off = c * DROWB + kh * 16;                // + 32 * step + digit * 32 * DROWB
+
   intx16 acc[2];
 #pragma unroll
   for (int d = 0; d < 2; ++d)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[d][v] = 0;
-  // DB k-steps (128-byte lines of every gathered row and digit) are fetched before use
-  for (int64_t k0 = 0; k0 < npad; k0 += 32 * DB) {
-    int4v a[DB][2];
-    uint4 q16[DB], cs16[DB];
+  int4v g[4][2];
+  uint4 q16[4], cs16[4];
+  auto fetch = [&](int64_t k0) {
 #pragma unroll
-    for (int t = 0; t < DB; ++t) {
+    for (int t = 0; t < 4; ++t) {
 #pragma unroll
-      for (int d = 0; d < 2; ++d) a[t][d] = *reinterpret_cast<const int4v*>(hrow + d * ps + k0 + 32 * t);
+      for (int d = 0; d < 2; ++d) g[t][d] = *reinterpret_cast<const int4v*>(grow[t] + d * ps + k0);
       q16[t] = *reinterpret_cast<const uint4*>(qrow + k0 + 32 * t);
       cs16[t] = *reinterpret_cast<const uint4*>(csrow + k0 + 32 * t);
     }
+  };
+  fetch(0);
+  for (int64_t k0 = 0; k0 < npad; k0 += 128) {
+    // the lines of this batch into LDS (only this wavefront touches its stage, and its LDS
+    // operations execute in order), the one-hot operands of the batch, then the next batch's loads
 #pragma unroll
-    for (int t = 0; t < DB; ++t) {
-      const int4v bf = onehot16(q16[t], brep, cs16[t]);
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-      for (int d = 0; d < 2; ++d) acc[d] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t][d], bf, acc[d], 0, 0, 0);
+      for (int d = 0; d < 2; ++d)
+        *reinterpret_cast<int4v*>(stage + d * 32 * DROWB + 8 * t * DROWB + wr_off) = g[t][d];
+    int4v bf[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) bf[t] = onehot16(q16[t], brep, cs16[t]);
+    if (k0 + 128 < npad) fetch(k0 + 128);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+#pragma unroll
+      for (int d = 0; d < 2; ++d) {
+        const int4v a = *reinterpret_cast<const int4v*>(stage + d * 32 * DROWB + rd_off + 32 * t);
+        acc[d] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bf[t], acc[d], 0, 0, 0);
+      }
     }
   }
   // fold: row r of the tile sits in register v = 4 (r / 8) + r % 4 of the lanes with kh = (r / 4) % 2
@@ -538,14 +569,15 @@ __global__ __launch_bounds__(256, 4) void t_delta_kernel(const int8_t* __restric
     }
   }
   // the chunk's A[a, b]: R of the lanes that own column "new b", element a, plus R of the lanes
-  // that own column "old a", element b (two lanes each: kh = 0, 1)
+  // that own column "old a", element b (two lanes each: kh = 0, 1); through the same piece of LDS
+  double* __restrict__ Rs = reinterpret_cast<double*>(stage);        // [lane][C], 8 KB at most
 #pragma unroll
-  for (int a2 = 0; a2 < C; ++a2) Rs[wave][lane][a2] = R[a2];
+  for (int a2 = 0; a2 < C; ++a2) Rs[lane * C + a2] = R[a2];
   __builtin_amdgcn_wave_barrier();
   for (int e = lane; e < C * C; e += 64) {
     const int a2 = e / C, b2 = e % C;
     Dpart[(int64_t)q * C * C + e] =
-        (Rs[wave][16 + b2][a2] + Rs[wave][48 + b2][a2]) + (Rs[wave][a2][b2] + Rs[wave][32 + a2][b2]);
+        (Rs[(16 + b2) * C + a2] + Rs[(48 + b2) * C + a2]) + (Rs[a2 * C + b2] + Rs[(32 + a2) * C + b2]);
   }
 }
 
