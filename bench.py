@@ -48,9 +48,10 @@ CLASS_KERNELS = {
     "cholesky": ("copy_lower_kernel", ["chol_panel_kernel", "gemm_f32_kernel", "syrk_f32_kernel", "fill_i32_kernel"]),
     "init": ("init_codebooks_kernel", ["convert_f16_f32_kernel"]),
     "update_s": ("update_S_kernel", ["rdiag_kernel"]),
-    "t_prep": ("t_split_kernel", ["t_diag_kernel", "t_rowscale_kernel"]),
-    "t_pad": ("pad_q_kernel", []),
+    "t_prep": ("t_split_kernel", ["t_diag_kernel", "t_rowscale_kernel", "t_symscale_kernel"]),
+    "t_pad": ("pad_q_kernel", ["t_flips_kernel", "t_chunks_kernel"]),
     "t_accum": ("t_accum_kernel", []),
+    "t_delta": ("t_delta_kernel", []),
     "t_solve": ("t_solve_kernel", []),
 }
 TRAFFIC_FILES = {"c3": "bench_c3_hbm_traffic.txt"}
