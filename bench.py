@@ -48,13 +48,14 @@ CLASS_KERNELS = {
     "cholesky": ("copy_lower_kernel", ["chol_panel_kernel", "gemm_f32_kernel", "syrk_f32_kernel", "fill_i32_kernel"]),
     "init": ("init_codebooks_kernel", ["convert_f16_f32_kernel"]),
     "update_s": ("update_S_kernel", ["rdiag_kernel"]),
+    "update_s32": ("update_S32_kernel", ["rdiag_kernel"]),
     "t_prep": ("t_split_kernel", ["t_diag_kernel", "t_rowscale_kernel", "t_symscale_kernel"]),
     "t_pad": ("pad_q_kernel", ["t_flips_kernel", "t_chunks_kernel"]),
     "t_accum": ("t_accum_kernel", []),
     "t_delta": ("t_delta_kernel", []),
     "t_solve": ("t_solve_kernel", []),
 }
-TRAFFIC_FILES = {"c3": "bench_c3_hbm_traffic.txt"}
+TRAFFIC_FILES = {"c3": "bench_c3_hbm_traffic.txt", "c5": "bench_c5_hbm_traffic.txt"}
 
 
 def load_traffic(config_name):
@@ -74,6 +75,8 @@ def load_traffic(config_name):
             continue
         total = sum(rows[k][0] * rows[k][1] for k in [main] + others if k in rows)
         out[cls] = total / rows[main][0]
+    if "update_s32" in out:          # the 32-row kernel is the S-update of the shapes that select it
+        out["update_s"] = out.pop("update_s32")
     # the two split-fp16 products (G = W H inside the solver, F = E H in the loss) share their kernels
     if "gemm_split_kernel" in rows:
         g = rows["gemm_split_kernel"][1]
