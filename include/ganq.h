@@ -41,7 +41,16 @@ extern "C" {
 
 typedef struct ganq_ctx ganq_ctx; /* opaque: one HIP device + one stream + workspace */
 
-typedef enum {
+/* The enumerations below cross the boundary as plain ints (the C rule).  A C++ translation unit
+ * gives them int as their fixed underlying type, so that an out-of-range value handed over by a C
+ * caller is a value the library can look at and reject rather than undefined behaviour. */
+#ifdef __cplusplus
+#define GANQ_ENUM enum : int
+#else
+#define GANQ_ENUM enum
+#endif
+
+typedef GANQ_ENUM {
   GANQ_OK = 0,
   GANQ_ERR_INVALID_ARG = 1,
   GANQ_ERR_UNSUPPORTED = 2,
@@ -50,10 +59,10 @@ typedef enum {
   GANQ_ERR_HIP = 5         /* HIP runtime failure; text in ganq_last_error */
 } ganq_status;
 
-typedef enum { GANQ_F16 = 0, GANQ_F32 = 1 } ganq_dtype;
+typedef GANQ_ENUM { GANQ_F16 = 0, GANQ_F32 = 1 } ganq_dtype;
 
 /* Which matrix is factorised (Eq. (10), Remark 3.1, Appendix A Eq. (23)-(24)). */
-typedef enum {
+typedef GANQ_ENUM {
   GANQ_PRECOND_NONE = 0,    /* H */
   GANQ_PRECOND_LAMBDA = 1,  /* H + lambda I */
   GANQ_PRECOND_DIAGDOM = 2, /* H + Diag(delta), delta_i = max(sum_j|H_ij| - 2 H_ii, 1e-8) */
@@ -61,14 +70,14 @@ typedef enum {
 } ganq_precond;
 
 /* Rule for the initial codebook T^0 (an input of Algorithm 1 the paper leaves open). */
-typedef enum {
+typedef GANQ_ENUM {
   GANQ_INIT_QUANTILE_MID = 0,       /* level s at row quantile (s + 1/2)/C, linear interpolation */
   GANQ_INIT_QUANTILE_ENDPOINTS = 1, /* level s at row quantile s/(C - 1) */
   GANQ_INIT_MINMAX_GRID = 2         /* C equally spaced values from row min to row max */
 } ganq_init;
 
 /* Value given to a code that no column of the row uses (Eq. (7), pseudo-inverse). */
-typedef enum {
+typedef GANQ_ENUM {
   GANQ_EMPTY_ZERO = 0, /* 0, the literal Moore-Penrose result */
   GANQ_EMPTY_KEEP = 1  /* keep the previous codebook entry */
 } ganq_empty;
@@ -83,7 +92,7 @@ typedef struct {
 } ganq_options;
 
 /* ganq_options.flags: sum S_i H S_i^T again in every sweep.  By default a sweep that changed few
- * indices (at most about 3.5 % of them, and at most max(256, n / 16) in any row) brings the
+ * indices (at most 1 in 24 of them, and at most about n / 2 - between 256 and 16384 - in any row) brings the
  * matrices of the previous sweep up to date from the changed columns instead - the same sums in
  * another order, kept in float64, so T^K may differ from the always-summing path in the last bits
  * of fp32 (and so may a near-tie of a later S-update). */
@@ -98,7 +107,8 @@ ganq_status ganq_create(ganq_ctx** out, int device, void* hip_stream);
 ganq_status ganq_destroy(ganq_ctx* ctx);
 
 /* Bytes of workspace that any call on a layer of this shape may need
- * (p_tokens = 0 when ganq_build_hessian is not used).  0 on invalid input. */
+ * (p_tokens = 0 when ganq_build_hessian is not used).  0 on invalid input and for
+ * shapes beyond what the calls accept (m or n above 65535, more than 2^40 tokens). */
 size_t ganq_workspace_bytes(int64_t m, int64_t n, int64_t p_tokens, int nbits);
 
 /* Hands the context a caller-owned device buffer (256-byte aligned).  It must
@@ -132,7 +142,7 @@ ganq_status ganq_build_hessian_tokens(ganq_ctx* ctx, const void* Xt, ganq_dtype 
 
 /* L = lower Cholesky factor of H (or of its preconditioned form), Eq. (10),
  * Remark 3.1, Appendix A.  L is n x n fp32 with the strict upper triangle
- * zeroed; L may not alias H.  *info_host: 0 on success, k > 0 if pivot k
+ * zeroed; L may not alias H.  *info_host (optional, may be NULL): 0 on success, k > 0 if pivot k
  * (1-based) was not finite or not above 8 sqrt(n) 2^-24 times the diagonal entry
  * of its column in the matrix being factorised (status GANQ_ERR_NOT_PD; L is
  * then unspecified).  The threshold is the size of the rounding noise of an fp32
@@ -255,7 +265,8 @@ ganq_status ganq_outlier_split_noalloc(ganq_ctx* ctx, const void* W, ganq_dtype 
  * of 32).  Codes: row i starts at packed + i * ldp bytes and is a little-endian
  * bit stream, code j in bits [N j, N j + N), bit b of the stream being bit
  * (b mod 8) of byte b / 8; unused bits up to ganq_packed_row_bytes() are zero.
- * ganq_packed_row_bytes = 4 N ceil(n / 32), rounded up to a multiple of 16. */
+ * ganq_packed_row_bytes = 4 N ceil(n / 32), rounded up to a multiple of 16
+ * (0 for n <= 0, n > 2^40 or N outside 1..4). */
 int64_t ganq_packed_row_bytes(int64_t n, int nbits);
 
 /* Q (m x n codes, device) and T (m x 2^N fp32, device) -> packed (m rows of ldp
@@ -280,7 +291,7 @@ ganq_status ganq_lut_gemv(ganq_ctx* ctx, const uint8_t* packed, int64_t ldp, con
 /* ---- optional per-kernel timing (measurement aid, not part of the method) ------ */
 
 /* Kernel classes the library launches; one step of Algorithm 1 touches all of them. */
-typedef enum {
+typedef GANQ_ENUM {
   GANQ_K_HESSIAN = 0,  /* H = X X^T product (+ partial-sum reduction) */
   GANQ_K_CHOLESKY = 1, /* whole blocked factorisation */
   GANQ_K_INIT = 2,     /* T^0 (and fp16 -> fp32 conversion of W) */
@@ -312,7 +323,8 @@ ganq_status ganq_profile_read(ganq_ctx* ctx, double* ms_host, int64_t* launches_
  * GANQ_OPT_FULL_T_UPDATE or a single sweep), and for sweep k < min(*sweeps_host, capacity):
  * log_host[3k] = 1 if it updated S_i H S_i^T from the changed columns, 0 if it summed it again;
  * log_host[3k+1] = the largest number of indices that changed in one row against the sweep
- * before; log_host[3k+2] = their total (both 0 for the first sweep).  log_host may be NULL. */
+ * before; log_host[3k+2] = their total (both 0 for the first sweep).  log_host may be NULL;
+ * capacity >= 0. */
 ganq_status ganq_sweep_log(const ganq_ctx* ctx, int32_t* log_host, int capacity, int* sweeps_host);
 
 /* Rates this GPU sustains on bare loops, for roofline fractions against measured rather than

@@ -59,6 +59,34 @@ def build(verbose=True, jobs=8):
     return LIB
 
 
+def build_sanitized(outdir, jobs=8):
+    """A copy of the library whose HOST code carries AddressSanitizer and UndefinedBehaviorSanitizer
+    instrumentation (device code is compiled as usual but at -O1: it is never run), for checking the
+    argument validation of the C ABI on a machine without a GPU.  Returns the path of the library."""
+    os.makedirs(outdir, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    flags = [f if f != "-O3" else "-O1" for f in FLAGS] + san
+
+    def one(src):
+        obj = os.path.join(outdir, os.path.splitext(src)[0] + ".o")
+        res = subprocess.run([_hipcc(), *flags, "-c", os.path.join(CSRC, src), "-o", obj],
+                             capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, res.stdout, res.stderr))
+        return obj
+
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        objs = list(pool.map(one, SOURCES))
+    lib = os.path.join(outdir, "libganq_san.so")
+    res = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address",
+                          "-fsanitize=undefined", "-Wno-option-ignored", "-o", lib, *objs],
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("link failed:\n%s\n%s" % (res.stdout, res.stderr))
+    return lib
+
+
 if __name__ == "__main__":
     build()
     sys.exit(0)

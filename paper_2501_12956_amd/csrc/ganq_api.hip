@@ -294,6 +294,8 @@ ganq_status ganq_destroy(ganq_ctx* ctx) {
 
 size_t ganq_workspace_bytes(int64_t m, int64_t n, int64_t p_tokens, int nbits) {
   if (m < 0 || n <= 0 || p_tokens < 0 || !nbits_ok(nbits)) return 0;
+  // shapes no call accepts; also keeps every product below within 64 bits
+  if (m > kMaxDim || n > kMaxDim || p_tokens > ((int64_t)1 << 40)) return 0;
   size_t q = quantize_scratch_bytes(m, n, nbits);
   size_t h = hessian_scratch_bytes(n, p_tokens > 0 ? p_tokens : 1) + kAlign;
   size_t h32 = align_up((size_t)n * n * sizeof(float)) + kAlign;
@@ -338,7 +340,7 @@ ganq_status ganq_outlier_split_noalloc(ganq_ctx* ctx, const void* W, ganq_dtype 
 }
 
 int64_t ganq_packed_row_bytes(int64_t n, int nbits) {
-  if (n <= 0 || nbits < 1 || nbits > 4) return 0;
+  if (n <= 0 || n > ((int64_t)1 << 40) || nbits < 1 || nbits > 4) return 0;
   return packed_row_bytes(n, nbits);
 }
 
@@ -418,7 +420,7 @@ ganq_status ganq_profile_read(ganq_ctx* ctx, double* ms_host, int64_t* launches_
 }
 
 ganq_status ganq_sweep_log(const ganq_ctx* ctx, int32_t* log_host, int capacity, int* sweeps_host) {
-  if (ctx == nullptr || sweeps_host == nullptr) return GANQ_ERR_INVALID_ARG;
+  if (ctx == nullptr || sweeps_host == nullptr || capacity < 0) return GANQ_ERR_INVALID_ARG;
   *sweeps_host = ctx->sweep_log_len;
   if (log_host == nullptr) return GANQ_OK;
   for (int k = 0; k < ctx->sweep_log_len && k < capacity; ++k)
