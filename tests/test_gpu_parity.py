@@ -468,6 +468,48 @@ def test_update_T_magnitude_and_diagonal_H(ctx):
     assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
 
 
+@pytest.mark.parametrize("eps,loss_tol", [(1e-2, 1e-5), (1e-3, 1e-4), (1e-4, 1e-2)])
+def test_update_T_ill_conditioned_rows(ctx, eps, loss_tol):
+    """Features that are copies of one signal plus noise of relative variance eps make every
+    S_i H S_i^T nearly rank one: cond(A_i) is about 1e5, 1e6, 1e7 for eps = 1e-2, 1e-3, 1e-4.  The
+    codebook is then determined only up to (input rounding) x cond, so T itself is compared with what
+    a plain float32 evaluation of A_i and b_i (float64 solve) achieves on the same rows, and the
+    quantity that is well determined - the objective of Eq. (9) at the returned codebook - against
+    the oracle's optimum."""
+    m, n, nbits, p = 24, 512, 4, 4096
+    C = 1 << nbits
+    rng = np.random.default_rng(5)
+    common = rng.standard_normal(p)
+    X = common[None, :] * (1 + 0.2 * rng.standard_normal((n, 1))) + np.sqrt(eps) * rng.standard_normal((n, p))
+    H32 = (X @ X.T).astype(np.float32)
+    W = (0.02 * rng.standard_normal((m, n))).astype(np.float32)
+    Q = rng.integers(0, C, (m, n)).astype(np.uint8)
+    H64, W64 = H32.astype(np.float64), W.astype(np.float64)
+    Tref, _ = ref.update_T(W64, H64, Q, nbits)
+    Tg = ctx.update_T(dev(W), dev(H32), dev(Q), dev(np.zeros((m, C), np.float32)), nbits)
+    Tg = (Tg[0] if isinstance(Tg, tuple) else Tg).cpu().numpy().astype(np.float64)
+    # the same rows with A_i and b_i summed in float32 (what a straightforward fp32 program has)
+    G32 = W @ H32
+    T32 = np.zeros_like(Tref)
+    conds = []
+    for i in range(m):
+        S32 = ref.one_hot(Q[i], C).astype(np.float32)
+        A32 = (S32 @ H32) @ S32.T
+        b32 = G32[i] @ S32.T
+        T32[i] = np.linalg.solve(A32.astype(np.float64), b32.astype(np.float64))
+        S = S32.astype(np.float64)
+        conds.append(np.linalg.cond(S @ H64 @ S.T))
+    scale = np.abs(Tref).max()
+    err_g, err_32 = np.abs(Tg - Tref).max() / scale, np.abs(T32 - Tref).max() / scale
+    _, l_ref = ref.layer_loss(W64, H64, Tref, Q)
+    _, l_g = ref.layer_loss(W64, H64, Tg, Q)
+    excess = ((l_g - l_ref) / l_ref).max()
+    print("T-update, cond(A_i) %.1e..%.1e: |T - oracle| / |T| = %.2e (plain float32: %.2e), "
+          "objective above the optimum by %.2e relative" % (min(conds), max(conds), err_g, err_32, excess))
+    assert err_g <= 3.0 * err_32 + 1e-6
+    assert excess <= loss_tol
+
+
 def test_update_T_empty_codes(ctx):
     from paper_2501_12956_amd import binding as b
     m, n, nbits = 6, 96, 3
