@@ -411,11 +411,13 @@ def _structured_H(kind, n, seed):
     p = 4096
     Z = rng.standard_normal((n, p))
     f = rng.standard_normal((1, p))
-    rho = {"weak": 0.0, "medium": 0.4, "strong": 0.8, "wide": 0.0, "mixed": 0.0, "dead": 0.3}[kind]
+    rho = {"weak": 0.0, "medium": 0.4, "strong": 0.8, "wide": 0.0, "vwide": 0.2, "mixed": 0.0, "dead": 0.3}[kind]
     X = np.sqrt(1 - rho) * Z + np.sqrt(rho) * f
     d = np.exp(rng.uniform(np.log(0.5), np.log(8.0), size=n))
     if kind == "wide":
         d = np.exp(rng.uniform(np.log(1e-2), np.log(1e3), size=n))
+    if kind == "vwide":       # eight decades of feature scale: H spans 2^53
+        d = np.exp(rng.uniform(np.log(1e-4), np.log(1e4), size=n))
     if kind == "mixed":
         X[n // 2:] = np.sqrt(0.1) * Z[n // 2:] + np.sqrt(0.9) * f
     if kind == "dead":
@@ -427,7 +429,7 @@ def _structured_H(kind, n, seed):
 @pytest.mark.parametrize("kind,nbits,m,n", [(k, b, 40, 300) for b in (3, 4)
                                             for k in ("weak", "strong", "wide", "mixed", "dead")]
                          + [("medium", 4, 16, 1100), ("mixed", 3, 70, 1100), ("weak", 2, 130, 700),
-                            ("wide", 2, 168, 43), ("wide", 1, 60, 90)])
+                            ("wide", 2, 168, 43), ("wide", 1, 60, 90), ("vwide", 4, 40, 300), ("vwide", 3, 33, 520)])
 def test_update_T_structured_H(ctx, kind, nbits, m, n):
     H32 = _structured_H(kind, n, 11)
     rng = np.random.default_rng(12)
@@ -439,6 +441,25 @@ def test_update_T_structured_H(ctx, kind, nbits, m, n):
     err = np.abs(Tg - Tref).max(axis=1) / np.abs(Tref).max(axis=1)
     print("T-update, %s H %dx%d, N=%d: max row error %.2e" % (kind, m, n, nbits, err.max()))
     assert np.all(err <= 1e-4)
+
+
+@pytest.mark.parametrize("kind", ["wide", "vwide", "strong"])
+def test_layer_loss_structured_H(ctx, kind):
+    """The two split-fp16 products (F = E H of the loss here) scale H by one power of two for the
+    whole matrix; feature scales spread over five and eight decades must not cost accuracy in the
+    objective, nor in its per-row values."""
+    m, n, nbits = 40, 300, 4
+    H32 = _structured_H(kind, n, 21)
+    rng = np.random.default_rng(22)
+    W = (rng.standard_normal((m, n)) * 0.02).astype(np.float32)
+    T0 = ref.init_codebooks(W, nbits).astype(np.float32)
+    Q = rng.integers(0, 1 << nbits, size=(m, n)).astype(np.uint8)
+    loss, rows = ctx.layer_loss(dev(W), dev(H32), dev(T0), dev(Q), nbits, want_rows=True)
+    lref, rref = ref.layer_loss(W, H32, T0, Q)
+    rel = np.abs(rows.cpu().numpy() - rref) / np.abs(rref)
+    print("loss, %s H: total off by %.2e relative, worst row %.2e" % (kind, abs(loss - lref) / lref, rel.max()))
+    assert abs(loss - lref) <= 1e-5 * lref
+    assert rel.max() <= 1e-4
 
 
 def test_update_T_magnitude_and_diagonal_H(ctx):
