@@ -133,9 +133,13 @@ ganq_status ganq_build_hessian(ganq_ctx* ctx, const void* X, ganq_dtype x_dtype,
 /* The same H = X X^T for activations stored the way calibration batches arrive
  * (Section 4.1 Setup: sequences of tokens through the layer): Xt is p x n
  * (tokens x features) row-major with leading dimension ldxt >= n, so
- * H = Xt^T Xt.  Any p >= 0 and any ldxt >= n.  The chunk is transposed into
- * workspace (at most 32768 tokens at a time, zero-padded to a multiple of 8)
- * and then takes the path of ganq_build_hessian; accumulate as there. */
+ * H = Xt^T Xt.  Any p >= 0 and any ldxt >= n.  fp16 activations with
+ * n % 8 == 0, ldxt % 8 == 0 and a 16-byte aligned Xt are read in place by the
+ * product (LDS transpose reads; the result equals ganq_build_hessian on the
+ * transposed array bit for bit).  Anything else is transposed into workspace
+ * in chunks (at most 32768 tokens at a time unless the workspace holds more,
+ * zero-padded to a multiple of 8) and then takes the path of
+ * ganq_build_hessian; accumulate as there. */
 ganq_status ganq_build_hessian_tokens(ganq_ctx* ctx, const void* Xt, ganq_dtype x_dtype, int64_t n,
                                       int64_t p, int64_t ldxt, float* H, int64_t ldh,
                                       int accumulate);

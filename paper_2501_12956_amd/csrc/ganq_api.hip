@@ -533,6 +533,17 @@ ganq_status ganq_build_hessian_tokens(ganq_ctx* ctx, const void* Xt, ganq_dtype 
   if (st != GANQ_OK) return st;
   hipStream_t s = ctx->stream;
   const int eb = (x_dtype == GANQ_F16) ? 2 : 4;
+  if (x_dtype == GANQ_F16 && hessian_tokens_direct_ok(Xt, n, p, ldxt)) {
+    // the product reads the token-major array as it is (transposing LDS reads): no copy
+    ctx->tprep.valid = false;
+    Arena ar(ctx->ws, ctx->ws_bytes);
+    float* part = (float*)ar.take(hessian_scratch_bytes(n, p));
+    if (part == nullptr) return fail(ctx, GANQ_ERR_WORKSPACE, "workspace too small for H = Xt^T Xt");
+    ProfScope prof(ctx, GANQ_K_HESSIAN);
+    GANQ_HIP(ctx, launch_hessian_f16_tokens(s, (const _Float16*)Xt, n, p, ldxt, H, ldh, accumulate, part));
+    ctx->last_error.clear();
+    return GANQ_OK;
+  }
   // Tokens per transposed chunk: what the workspace holds beyond the scratch of the product
   // (at least kTokenChunk, which ganq_workspace_bytes guarantees; a larger workspace means
   // fewer, larger products).

@@ -134,6 +134,9 @@ inline int64_t pad_rows(int64_t m) { return ceil_div(m, kSlabRows) * kSlabRows; 
 int hessian_split(int64_t n, int64_t p);
 size_t hessian_scratch_bytes(int64_t n, int64_t p);
 constexpr int64_t kTokenChunk = 32768;   // tokens transposed at a time by the token-major entry point
+bool hessian_tokens_direct_ok(const void* Xt, int64_t n, int64_t p, int64_t ldxt);
+hipError_t launch_hessian_f16_tokens(hipStream_t s, const _Float16* Xt, int64_t n, int64_t p, int64_t ldxt,
+                                     float* H, int64_t ldh, int accumulate, float* partials);
 hipError_t launch_transpose_tokens(hipStream_t s, const void* Xt, int elem_bytes, int64_t pc, int64_t n,
                                    int64_t ldxt, void* Xn, int64_t ldn);
 size_t update_s_scratch_bytes(int64_t m, int64_t n);

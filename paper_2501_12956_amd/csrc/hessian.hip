@@ -28,7 +28,21 @@ constexpr int HSTAGEB = 2 * HTILEB;          // A rows + B rows
 constexpr int HNW = 8;          // wavefronts: 2 x 4, each 128 x 64 of the tile
 constexpr int HDPW = (HT / 8) / HNW;         // direct loads per wavefront, operand and stage
 
+constexpr int TROWB = HT * 2;   // token-major stage: bytes per token row (256 features)
+
 typedef int int4v __attribute__((ext_vector_type(4)));
+typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+
+// Eight consecutive tokens of one feature from a token-major stage: two transpose reads, tokens
+// 0..3 at p and 4..7 four token rows further on.
+__device__ inline half8 tr_fragment(const unsigned char* p) {
+  typedef short short4v __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) short4v lds_short4;
+  const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(uintptr_t)p);
+  const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(uintptr_t)(p + 4 * TROWB));
+  return __builtin_shufflevector(__builtin_bit_cast(half4v, lo), __builtin_bit_cast(half4v, hi), 0, 1, 2, 3, 4,
+                                 5, 6, 7);
+}
 
 // One wavefront-wide direct load: lane l's 16 bytes land at LDS byte lds_addr + 16 l.
 // The compiler does not see these loads, so its own vmcnt waits can only be too early for
@@ -98,6 +112,18 @@ __device__ inline void zorder_tile(int t, int nt, int& bm, int& bn) {
 // tiles of 32 x 32 (128 accumulator registers).  Two LDS stages of 64 tokens, one barrier
 // per stage: after the barrier the loads of the next stage are issued into the buffer that
 // every wavefront has just finished reading, then the current stage is multiplied.
+//
+// TOK: X is the token-major array Xt (p x n, tokens x features, leading dimension ldx) and
+// H = Xt^T Xt.  A stage then holds 64 token rows of 256 features per operand (512-byte rows), and
+// the MFMA fragments - 8 consecutive tokens of one feature per lane - are gathered by the LDS
+// transpose reads of gfx950 (ds_read_b64_tr_b16: within 16 lanes, lane 4a + b receives element b of
+// the 8-byte pieces addressed by lanes a, 4 + a, 8 + a, 12 + a).  Lane 4e + a of a group of 16
+// addresses token e of a run of four and features 4a .. 4a + 3 of a run of 16, so lane f of the
+// group ends up with tokens 0..3 of feature f.  Both operands take the same path, so the order in
+// which tokens land in a fragment is the same on both sides of every product.  16-byte chunk c of
+// token row t is stored at position c ^ 2 (t & 3): the four token rows a group reads then fall
+// into four different 32-byte bank groups.
+template <bool TOK>
 __global__ __launch_bounds__(64 * HNW) void hessian_f16_kernel(const _Float16* __restrict__ X, int64_t n,
                                                               int64_t p, int64_t ldx, int64_t chunk,
                                                               int nt, int ntiles, int ngroups, int gsz,
@@ -126,30 +152,71 @@ __global__ __launch_bounds__(64 * HNW) void hessian_f16_kernel(const _Float16* _
   const int kh = lane >> 5, l32 = lane & 31;
   const int64_t m0 = (int64_t)bm * HT, n0 = (int64_t)bn * HT;
 
-  // descriptors over the row blocks of the two operands: rows >= n read as zero
-  const int64_t rowsA = (n - m0 < HT) ? n - m0 : HT, rowsB = (n - n0 < HT) ? n - n0 : HT;
-  const int4v rsA = make_rsrc(X + m0 * ldx, ((rowsA - 1) * ldx + p) * 2);
-  const int4v rsB = make_rsrc(X + n0 * ldx, ((rowsB - 1) * ldx + p) * 2);
-
-  // One direct load covers 8 rows x 128 bytes: lane -> row (lane / 8) and LDS chunk position
-  // (lane % 8), which holds chunk position ^ (row & 7) of the row.
-  const int dr = lane >> 3;
-  const int dc = (lane & 7) ^ dr;
-  uint32_t voff[HDPW];
-#pragma unroll
-  for (int j = 0; j < HDPW; ++j)
-    voff[j] = (uint32_t)(((int64_t)((wave + HNW * j) * 8 + dr) * ldx + dc * 8) * 2);
-  const int64_t klane = dc * 8;
-
-  auto issue = [&](int64_t k0, int st) {
-    const bool ok = k0 + klane < kend;     // p % 8 == 0: a chunk is wholly inside or outside
-    const uint32_t soff = (uint32_t)(k0 * 2);
-    const uint32_t sbase = lds0 + st * HSTAGEB;
+  int4v rsA, rsB;
+  uint32_t voff[HDPW], voffB[HDPW];
+  int64_t klane = 0;          // !TOK: first token of this lane's chunk within a stage
+  int tlane[HDPW];            // TOK: token row of this lane's chunk within a stage
+  if constexpr (!TOK) {
+    // descriptors over the row blocks of the two operands: rows >= n read as zero
+    const int64_t rowsA = (n - m0 < HT) ? n - m0 : HT, rowsB = (n - n0 < HT) ? n - n0 : HT;
+    rsA = make_rsrc(X + m0 * ldx, ((rowsA - 1) * ldx + p) * 2);
+    rsB = make_rsrc(X + n0 * ldx, ((rowsB - 1) * ldx + p) * 2);
+    // One direct load covers 8 rows x 128 bytes: lane -> row (lane / 8) and LDS chunk position
+    // (lane % 8), which holds chunk position ^ (row & 7) of the row.
+    const int dr = lane >> 3;
+    const int dc = (lane & 7) ^ dr;
 #pragma unroll
     for (int j = 0; j < HDPW; ++j) {
-      const uint32_t vo = ok ? voff[j] : 0x80000000u;   // beyond any descriptor: reads zero
-      load16_to_lds(rsA, sbase + (wave + HNW * j) * 1024, vo, soff);
-      load16_to_lds(rsB, sbase + HTILEB + (wave + HNW * j) * 1024, vo, soff);
+      voff[j] = (uint32_t)(((int64_t)((wave + HNW * j) * 8 + dr) * ldx + dc * 8) * 2);
+      voffB[j] = voff[j];
+      tlane[j] = 0;
+    }
+    klane = dc * 8;
+  } else {
+    // Descriptors from (first token of this split, first feature of the block) to the end of Xt, at
+    // most 2 GiB, which holds every offset a load of this split uses (checked by the host).  What
+    // is read is decided per lane, not by the descriptor: chunks of tokens >= kend and of features
+    // >= n (n % 8 == 0, so a chunk is wholly inside or outside) get an offset beyond any descriptor
+    // and read zero, so no byte outside Xt's p x n elements is touched.
+    const int64_t endel = (p - 1) * ldx + n;                        // elements of Xt that exist
+    auto span = [&](int64_t base) {
+      const int64_t b = (endel - base) * 2;
+      return b <= 0 ? (int64_t)0 : (b > 0x80000000ll ? (int64_t)0x80000000ll : b);
+    };
+    rsA = make_rsrc(X + kbeg * ldx + m0, span(kbeg * ldx + m0));
+    rsB = make_rsrc(X + kbeg * ldx + n0, span(kbeg * ldx + n0));
+    // One direct load covers 2 token rows x 512 bytes: lane -> token row (lane / 32) and LDS
+    // chunk position (lane % 32), which holds chunk position ^ 2 (token & 3) of the row.
+#pragma unroll
+    for (int j = 0; j < HDPW; ++j) {
+      const int tl = 2 * (wave + HNW * j) + (lane >> 5);
+      const int cg = (lane & 31) ^ (2 * (tl & 3));
+      const uint32_t vo = (uint32_t)(((int64_t)tl * ldx + cg * 8) * 2);
+      voff[j] = (m0 + cg * 8 < n) ? vo : 0x80000000u;
+      voffB[j] = (n0 + cg * 8 < n) ? vo : 0x80000000u;
+      tlane[j] = tl;
+    }
+  }
+
+  auto issue = [&](int64_t k0, int st) {
+    const uint32_t sbase = lds0 + st * HSTAGEB;
+    if constexpr (!TOK) {
+      const bool ok = k0 + klane < kend;     // p % 8 == 0: a chunk is wholly inside or outside
+      const uint32_t soff = (uint32_t)(k0 * 2);
+#pragma unroll
+      for (int j = 0; j < HDPW; ++j) {
+        const uint32_t vo = ok ? voff[j] : 0x80000000u;   // beyond any descriptor: reads zero
+        load16_to_lds(rsA, sbase + (wave + HNW * j) * 1024, vo, soff);
+        load16_to_lds(rsB, sbase + HTILEB + (wave + HNW * j) * 1024, vo, soff);
+      }
+    } else {
+      const uint32_t soff = (uint32_t)((k0 - kbeg) * ldx * 2);      // below 2^31: checked by the host
+#pragma unroll
+      for (int j = 0; j < HDPW; ++j) {
+        const bool ok = k0 + tlane[j] < kend;
+        load16_to_lds(rsA, sbase + (wave + HNW * j) * 1024, ok ? voff[j] : 0x80000000u, soff);
+        load16_to_lds(rsB, sbase + HTILEB + (wave + HNW * j) * 1024, ok ? voffB[j] : 0x80000000u, soff);
+      }
     }
   };
 
@@ -162,6 +229,19 @@ __global__ __launch_bounds__(64 * HNW) void hessian_f16_kernel(const _Float16* _
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int rswz = l32 & 7;
+  // TOK: byte offset, inside a stage, of this lane's 8-byte piece for each of the wavefront's
+  // fragments: token row 8 (lane / 32) + e, chunk (feature / 8) ^ 2 e, half chunk a & 1
+  uint32_t toffA[4], toffB[2];
+  {
+    const int s16 = lane & 15, e = s16 >> 2, a = s16 & 3, g1 = (lane >> 4) & 1;
+    const uint32_t rowb = (uint32_t)((8 * kh + e) * TROWB + 8 * (a & 1));
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      toffA[i] = rowb + (uint32_t)(((wr * 16 + i * 4 + 2 * g1 + (a >> 1)) ^ (2 * e)) * 16);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      toffB[j] = rowb + (uint32_t)(((wc * 8 + j * 4 + 2 * g1 + (a >> 1)) ^ (2 * e)) * 16);
+  }
   const int nk = (int)((kend - kbeg + HK - 1) / HK);
   if (nk > 0) issue(kbeg, 0);
   int st = 0;
@@ -175,13 +255,22 @@ __global__ __launch_bounds__(64 * HNW) void hessian_f16_kernel(const _Float16* _
 #pragma unroll
     for (int ks = 0; ks < HK / 16; ++ks) {
       half8 af[4], bfr[2];
-      const int cpos = ((2 * ks + kh) ^ rswz) * 16;
+      if constexpr (!TOK) {
+        const int cpos = ((2 * ks + kh) ^ rswz) * 16;
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        af[i] = *reinterpret_cast<const half8*>(As + (wr * 128 + i * 32 + l32) * HROWB + cpos);
+        for (int i = 0; i < 4; ++i)
+          af[i] = *reinterpret_cast<const half8*>(As + (wr * 128 + i * 32 + l32) * HROWB + cpos);
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-        bfr[j] = *reinterpret_cast<const half8*>(Bs + (wc * 64 + j * 32 + l32) * HROWB + cpos);
+        for (int j = 0; j < 2; ++j)
+          bfr[j] = *reinterpret_cast<const half8*>(Bs + (wc * 64 + j * 32 + l32) * HROWB + cpos);
+      } else {
+        const unsigned char* Ak = As + ks * (16 * TROWB);
+        const unsigned char* Bk = Bs + ks * (16 * TROWB);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) af[i] = tr_fragment(Ak + toffA[i]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bfr[j] = tr_fragment(Bk + toffB[j]);
+      }
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -296,10 +385,45 @@ hipError_t launch_hessian_f16(hipStream_t s, const _Float16* X, int64_t n, int64
   dim3 grid((unsigned)(8 * ceil_div((int64_t)ngroups * split, 8) * 32));
   static std::atomic<uint64_t> lds_set{0};
   {
-    const hipError_t ea = ensure_dynamic_lds((const void*)hessian_f16_kernel, HS * HSTAGEB, lds_set);
+    const hipError_t ea = ensure_dynamic_lds((const void*)hessian_f16_kernel<false>, HS * HSTAGEB, lds_set);
     if (ea != hipSuccess) return ea;
   }
-  hipLaunchKernelGGL(hessian_f16_kernel, grid, dim3(64 * HNW), HS * HSTAGEB, s, X, n, p, ldx, chunk,
+  hipLaunchKernelGGL(hessian_f16_kernel<false>, grid, dim3(64 * HNW), HS * HSTAGEB, s, X, n, p, ldx, chunk,
+                     (int)nt, ntiles, ngroups, gsz, split, partials);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  dim3 g2((unsigned)ceil_div(n, 32), (unsigned)ceil_div(n, 32));
+  hipLaunchKernelGGL(reduce_mirror_kernel, g2, dim3(256), 0, s, H, n, ldh, partials, n, split,
+                     accumulate);
+  return hipGetLastError();
+}
+
+// Whether the token-major product can take Xt as it is: 16-byte aligned rows, whole 16-byte chunks
+// of features, and a token split whose byte extent fits the 32-bit offsets of the loads.
+bool hessian_tokens_direct_ok(const void* Xt, int64_t n, int64_t p, int64_t ldxt) {
+  if (p <= 0 || (((uintptr_t)Xt) & 15) != 0 || (ldxt % 8) != 0 || (n % 8) != 0) return false;
+  if (ldxt >= ((int64_t)1 << 23)) return false;       // 64 token rows within 31-bit lane offsets
+  const int split = hessian_split(n, p);
+  const int64_t chunk = ceil_div(ceil_div(p, split), HK) * HK;
+  return (chunk + HK) * ldxt * 2 <= ((int64_t)1 << 31);
+}
+
+// H (+)= Xt^T Xt straight from the token-major array; requires hessian_tokens_direct_ok.
+hipError_t launch_hessian_f16_tokens(hipStream_t s, const _Float16* Xt, int64_t n, int64_t p, int64_t ldxt,
+                                     float* H, int64_t ldh, int accumulate, float* partials) {
+  if (!hessian_tokens_direct_ok(Xt, n, p, ldxt)) return hipErrorInvalidValue;
+  const int split = hessian_split(n, p);
+  const int64_t chunk = ceil_div(ceil_div(p, split), HK) * HK;
+  const int64_t nt = ceil_div(n, HT);
+  const int ntiles = (int)(nt * (nt + 1) / 2);
+  const int ngroups = (int)ceil_div(ntiles, 32), gsz = (int)ceil_div(ntiles, ngroups);
+  dim3 grid((unsigned)(8 * ceil_div((int64_t)ngroups * split, 8) * 32));
+  static std::atomic<uint64_t> lds_set{0};
+  {
+    const hipError_t ea = ensure_dynamic_lds((const void*)hessian_f16_kernel<true>, HS * HSTAGEB, lds_set);
+    if (ea != hipSuccess) return ea;
+  }
+  hipLaunchKernelGGL(hessian_f16_kernel<true>, grid, dim3(64 * HNW), HS * HSTAGEB, s, Xt, n, p, ldxt, chunk,
                      (int)nt, ntiles, ngroups, gsz, split, partials);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

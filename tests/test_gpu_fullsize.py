@@ -64,6 +64,25 @@ def test_full_hessian_sampled_entries(layer):
     assert torch.equal(Hc, Hc.T)
 
 
+def test_full_hessian_from_token_major_activations(layer):
+    """The same H from the activations stored tokens x features, which the product reads in place:
+    it takes the tokens in the same order as the feature-major product, so the two agree to the
+    bit, and the feature-major one is checked against float64 dot products above."""
+    cfg, ctx, X, H = layer["cfg"], layer["ctx"], layer["X"], layer["H"]
+    Xt = X.t().contiguous()
+    Ht = ctx.build_hessian_tokens(Xt)
+    assert torch.equal(Ht, H)
+    # accumulation over two token ranges of uneven size: not bit-identical (other partial sums)
+    cut = 100003 // 8 * 8
+    H2 = ctx.build_hessian_tokens(Xt[:cut])
+    H2 = ctx.build_hessian_tokens(Xt[cut:], H=H2, accumulate=True)
+    d = H.diagonal().sqrt()
+    rel = ((H2 - H).abs() / (d[:, None] * d[None, :])).max().item()
+    print("full-size token-major H in two ranges: max |dH|/sqrt(HjjHkk) = %.2e" % rel)
+    assert rel <= h_tol(cfg.p)
+    del Xt
+
+
 def test_full_cholesky(layer):
     H64 = layer["H"].cpu().numpy().astype(np.float64)
     L64 = layer["L"].cpu().numpy().astype(np.float64)

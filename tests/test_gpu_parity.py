@@ -112,6 +112,13 @@ def test_hessian_fp32_and_strided(ctx):
 
 @pytest.mark.parametrize("n,p,dtype", [(300, 1093, torch.float16), (130, 5, torch.float16),
                                        (200, 515, torch.float32),
+                                       # n % 8 == 0 and aligned rows: the product reads Xt as it is
+                                       # (transposing LDS reads), no transposed copy; several feature
+                                       # blocks with a ragged last one, fewer tokens than one stage,
+                                       # token counts that are no multiple of anything
+                                       (304, 1093, torch.float16), (520, 2500, torch.float16),
+                                       (256, 37, torch.float16), (1032, 777, torch.float16),
+                                       (64, 20011, torch.float16),
                                        # more than 2^22 tokens with room to transpose them all at once: the
                                        # fp16 product takes chunks whose leading dimension stays below 2^22
                                        (8, (1 << 22) + 4104, torch.float16)])
