@@ -408,6 +408,14 @@ __global__ __launch_bounds__(64 * NW) void update_S_kernel(const float* __restri
       if (b > 0) {
         const Far Fe = far_setup(j0 - SB, kearly_next, n, wv - 4, NW - 4);
         far_run(Fe, mearly, false);
+        // their share of what remains of that far part starts with rows that are final too:
+        // requested now, the fragments arrive while the sequential phase finishes
+        const Far Fn = far_setup(j0 - SB, j0, kearly_next, wv, NW);
+        if (Fn.active && Fn.nch >= 2) {
+#pragma unroll
+          for (int u = 0; u < PU; ++u) fa[u] = far_fetch(Fn, u);
+          prefetched = true;
+        }
       }
     }
     kearly = kearly_next;
