@@ -311,6 +311,9 @@ def main():
     ap.add_argument("--nbits", type=int, default=4, help="--decode only: bits per stored code")
     ap.add_argument("--stacked", action="store_true",
                     help="time three layers that share their activations: three calls against one stacked call")
+    ap.add_argument("--token-major", action="store_true",
+                    help="hand the activations over as tokens x features (H = Xt^T Xt, read in place) instead "
+                         "of features x tokens; everything else as in the default step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the solver has no multi-GPU path); "
@@ -337,9 +340,13 @@ def main():
     H = torch.empty(n, n, dtype=torch.float32, device=dev)
     Q = torch.empty(m, n, dtype=torch.uint8, device=dev)
     state = {}
+    Xt = X.t().contiguous() if args.token_major else None
 
     def step():
-        ctx.build_hessian(X, H=H)
+        if Xt is not None:
+            ctx.build_hessian_tokens(Xt, H=H)
+        else:
+            ctx.build_hessian(X, H=H)
         # Cholesky, T^0 and the alternations in one call: the library factors H itself and runs what
         # does not need L (W to fp32, T^0, G = W H, the split of H) beside the factorisation
         T, _ = ctx.quantize_layer(W, H, cfg.nbits, cfg.iters, Q=Q)
@@ -434,10 +441,12 @@ def main():
         "dtype": "f32 (H build: f16 x f16 -> f32; T-update sums: exact int32 over base-256 int8 digits of H; "
                  "G = W H and the loss product: two-piece f16 splits, f32 accumulate; per-row solve: f64)",
         "data": "synthetic",
-        "config": {"workload": "%s: W %dx%d %s, X %dx%d %s, N=%d bits, %d alternations; step = H build + "
+        "config": {"workload": "%s: W %dx%d %s, X %dx%d %s%s, N=%d bits, %d alternations; step = H build + "
                                "Cholesky + codebook init + alternations + loss"
                                % (cfg.name, m, n, str(cfg.w_dtype).replace("torch.", ""), n, p,
-                                  str(cfg.x_dtype).replace("torch.", ""), cfg.nbits, cfg.iters)},
+                                  str(cfg.x_dtype).replace("torch.", ""),
+                                  " (handed over as tokens x features)" if args.token_major else "",
+                                  cfg.nbits, cfg.iters)},
         "final_loss": state["loss"],
         "roofline": roofline,
         "kernels": kernels,
