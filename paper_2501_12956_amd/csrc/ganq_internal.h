@@ -56,6 +56,28 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 
+typedef int int4v __attribute__((ext_vector_type(4)));
+
+// Raw buffer descriptor over [base, base + bytes): a load whose offset falls outside reads zero.
+__device__ inline int4v make_rsrc(const void* base, int64_t bytes) {
+  const uint64_t ad = (uint64_t)(uintptr_t)base;
+  int4v r;
+  r[0] = (int)(uint32_t)ad;
+  r[1] = (int)(uint32_t)((ad >> 32) & 0xffffu);
+  r[2] = (int)(uint32_t)bytes;
+  r[3] = 0x00020000;
+  return r;
+}
+// One wavefront-wide load from global memory straight into LDS: lane l's 16 bytes land at LDS
+// byte lds_addr + 16 l.  The compiler does not see these loads, so its own vmcnt waits can only
+// be too early for them, never for its own loads (the counter retires in order); a kernel waits
+// for them explicitly (wait_all_loads) before the barrier that publishes a stage.
+__device__ inline void load16_to_lds(int4v rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+__device__ inline void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 constexpr int64_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + (kAlign - 1)) & ~(size_t)(kAlign - 1); }
 __host__ __device__ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

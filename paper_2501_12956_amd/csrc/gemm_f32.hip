@@ -152,13 +152,6 @@ constexpr int STILEB = 128 * SROWB;
 constexpr int SSTAGEB = 2 * STILEB;
 constexpr int SYRK_LDS = 2 * SSTAGEB;
 
-typedef int int4v __attribute__((ext_vector_type(4)));
-
-__device__ inline void syrk_load16_to_lds(int4v rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
-}
-
 __global__ __launch_bounds__(256) void syrk_f32_kernel(int64_t M, const float* __restrict__ A, int64_t lda,
                                                        float* __restrict__ C, int64_t ldc) {
   // tile t of the lower triangle: row bm, column bn <= bm
@@ -201,8 +194,8 @@ __global__ __launch_bounds__(256) void syrk_f32_kernel(int64_t M, const float* _
     const uint32_t sb = lds0 + st * SSTAGEB;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      syrk_load16_to_lds(rsA, sb + (wave + 4 * j) * 1024, voff[j], soff);
-      syrk_load16_to_lds(rsB, sb + STILEB + (wave + 4 * j) * 1024, voff[j], soff);
+      load16_to_lds(rsA, sb + (wave + 4 * j) * 1024, voff[j], soff);
+      load16_to_lds(rsB, sb + STILEB + (wave + 4 * j) * 1024, voff[j], soff);
     }
   };
 

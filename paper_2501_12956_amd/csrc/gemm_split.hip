@@ -23,23 +23,6 @@ constexpr int GSTAGEB = 2 * GTILEB;
 constexpr int GNW = 8;
 constexpr int GDPW = (GT / 8) / GNW;
 
-typedef int int4v __attribute__((ext_vector_type(4)));
-
-__device__ inline void g_load16_to_lds(int4v rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
-}
-__device__ inline void g_wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-__device__ inline int4v g_make_rsrc(const void* base, int64_t bytes) {
-  const uint64_t ad = (uint64_t)(uintptr_t)base;
-  int4v r;
-  r[0] = (int)(uint32_t)ad;
-  r[1] = (int)(uint32_t)((ad >> 32) & 0xffffu);
-  r[2] = (int)(uint32_t)bytes;
-  r[3] = 0x00020000;
-  return r;
-}
-
 __global__ void fill_u32_kernel(unsigned* p, int count, unsigned v) {
   if ((int)threadIdx.x < count) p[threadIdx.x] = v;
 }
@@ -131,16 +114,16 @@ __global__ __launch_bounds__(64 * GNW) void gemm_split_kernel(const _Float16* __
   auto set_piece = [&](int p) {
     // piece pairs (A, B): (hi, hi), (hi, lo), (lo, hi)
     const int64_t pa = (p == 2) ? M : 0, pb = (p == 1) ? N : 0;
-    rsA = g_make_rsrc(As + (pa + m0) * k64, rowsA * k64 * 2);
-    rsB = g_make_rsrc(Bs + (pb + n0) * k64, rowsB * k64 * 2);
+    rsA = make_rsrc(As + (pa + m0) * k64, rowsA * k64 * 2);
+    rsB = make_rsrc(Bs + (pb + n0) * k64, rowsB * k64 * 2);
   };
   auto issue = [&](int s, int st) {
     const uint32_t soff = (uint32_t)((s % nk1) * GK * 2);
     const uint32_t sbase = lds0 + st * GSTAGEB;
 #pragma unroll
     for (int j = 0; j < GDPW; ++j) {
-      g_load16_to_lds(rsA, sbase + (wave + GNW * j) * 1024, voff[j], soff);
-      g_load16_to_lds(rsB, sbase + GTILEB + (wave + GNW * j) * 1024, voff[j], soff);
+      load16_to_lds(rsA, sbase + (wave + GNW * j) * 1024, voff[j], soff);
+      load16_to_lds(rsB, sbase + GTILEB + (wave + GNW * j) * 1024, voff[j], soff);
     }
   };
 
@@ -158,7 +141,7 @@ __global__ __launch_bounds__(64 * GNW) void gemm_split_kernel(const _Float16* __
   int st = 0;
 #pragma unroll 1
   for (int s = 0; s < nk; ++s) {
-    g_wait_all_loads();
+    wait_all_loads();
     __syncthreads();
     if (s + 1 < nk) {
       if ((s + 1) % nk1 == 0) set_piece((s + 1) / nk1);

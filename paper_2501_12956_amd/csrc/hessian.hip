@@ -30,7 +30,6 @@ constexpr int HDPW = (HT / 8) / HNW;         // direct loads per wavefront, oper
 
 constexpr int TROWB = HT * 2;   // token-major stage: bytes per token row (256 features)
 
-typedef int int4v __attribute__((ext_vector_type(4)));
 typedef _Float16 half4v __attribute__((ext_vector_type(4)));
 
 // Eight consecutive tokens of one feature from a token-major stage: two transpose reads, tokens
@@ -42,27 +41,6 @@ __device__ inline half8 tr_fragment(const unsigned char* p) {
   const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(uintptr_t)(p + 4 * TROWB));
   return __builtin_shufflevector(__builtin_bit_cast(half4v, lo), __builtin_bit_cast(half4v, hi), 0, 1, 2, 3, 4,
                                  5, 6, 7);
-}
-
-// One wavefront-wide direct load: lane l's 16 bytes land at LDS byte lds_addr + 16 l.
-// The compiler does not see these loads, so its own vmcnt waits can only be too early for
-// them, never for its own loads (the counter retires in order); the kernel waits for them
-// explicitly before the barrier that publishes a stage.
-__device__ inline void load16_to_lds(int4v rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
-}
-__device__ inline void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-// raw buffer descriptor over [base, base + bytes): loads beyond it return zero
-__device__ inline int4v make_rsrc(const void* base, int64_t bytes) {
-  const uint64_t ad = (uint64_t)(uintptr_t)base;
-  int4v r;
-  r[0] = (int)(uint32_t)ad;
-  r[1] = (int)(uint32_t)((ad >> 32) & 0xffffu);
-  r[2] = (int)(uint32_t)bytes;
-  r[3] = 0x00020000;
-  return r;
 }
 
 // Tiles (r, c), c <= r < nt, of the lower triangle in Z-order (bits of c and r interleaved, c

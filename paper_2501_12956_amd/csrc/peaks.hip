@@ -6,7 +6,6 @@
 namespace ganq {
 namespace {
 
-typedef int int4v __attribute__((ext_vector_type(4)));
 typedef int intx16 __attribute__((ext_vector_type(16)));
 
 // 4 independent accumulators per wavefront, 2 wavefronts per SIMD: back-to-back issue

@@ -422,7 +422,6 @@ __global__ __launch_bounds__(1024) void t_chunks_kernel(const int* __restrict__ 
   }
 }
 
-typedef int int4v __attribute__((ext_vector_type(4)));
 typedef int intx16 __attribute__((ext_vector_type(16)));
 
 // 16 one-hot operand bytes: byte t of word w is cs (the column factor 2^e_k) where the code byte
@@ -595,15 +594,6 @@ constexpr int T_ATILEB = TM * T_ROWB;
 constexpr int T_BTILEB = TN * T_ROWB;
 constexpr int T_STAGEB = T_ATILEB + T_BTILEB;
 constexpr int T_LDS_BYTES = T_S * T_STAGEB;
-
-// One wavefront-wide direct load: lane l's 16 bytes land at LDS byte lds_addr + 16 l.  The
-// compiler does not see these loads; the kernel waits for them (vmcnt) before the barrier
-// that publishes a stage.
-__device__ inline void load16_to_lds(int4v rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
-}
-__device__ inline void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <int V> struct IntC { static constexpr int value = V; };
 
