@@ -55,7 +55,7 @@ CLASS_KERNELS = {
     "t_delta": ("t_delta_kernel", []),
     "t_solve": ("t_solve_kernel", []),
 }
-TRAFFIC_FILES = {"c3": "bench_c3_hbm_traffic.txt", "c5": "bench_c5_hbm_traffic.txt"}
+TRAFFIC_FILES = {c: "bench_%s_hbm_traffic.txt" % c for c in ("c2", "c3", "c4a", "c4b", "c5", "c5_3")}
 
 
 def load_traffic(config_name):
