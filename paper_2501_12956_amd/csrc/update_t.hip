@@ -922,6 +922,9 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
                                                      double* __restrict__ Astate, int* __restrict__ Tlog,
                                                      const int* __restrict__ Cbase,
                                                      const double* __restrict__ Dpart,
+                                                     double* __restrict__ Vstate, int* __restrict__ Nstate,
+                                                     const uint32_t* __restrict__ Flist,
+                                                     const int* __restrict__ Fcnt,
                                                      int64_t mpad, const float* __restrict__ scale,
                                                      const float* __restrict__ Hdiag,
                                                      const float* __restrict__ G, int64_t ldg,
@@ -945,28 +948,57 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
     binB[a][tid] = 0.f;
     binC[a][tid] = 0;
   }
-  // 16 columns per lane are fetched before the first is binned: the row of G comes from HBM,
-  // and one column at a time would pay that latency n / 64 times over
-  for (int64_t j0 = 0; j0 < n; j0 += 64 * 16) {
-    int qa[16];
-    float hv[16], gv[16];
+  // After a sweep that brought S_i H0 S_i^T up to date from the changed columns, the per-code sums
+  // of the row (diagonal of H, G, counts) are brought up to date the same way: the state of the
+  // sweep before plus the signed contributions of the changed columns, instead of a pass over
+  // the whole row of G and Q.
+  const bool from_state = t_use_delta(Tstat, m_rows, n, fmax);
+  if (Tlog != nullptr && i == 0 && tid == 0) {
+    Tlog[0] = from_state ? 1 : 0;
+    Tlog[1] = Tstat[0];
+    Tlog[2] = Tstat[1];
+  }
+  if (!from_state) {
+    // 16 columns per lane are fetched before the first is binned: the row of G comes from HBM,
+    // and one column at a time would pay that latency n / 64 times over
+    for (int64_t j0 = 0; j0 < n; j0 += 64 * 16) {
+      int qa[16];
+      float hv[16], gv[16];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int64_t j = j0 + tid + 64 * u;
-      const int64_t jc = (j < n) ? j : n - 1;       // clamped: the loads stay unconditional
-      const int qv = Q[i * ldq + jc];
-      qa[u] = (j < n) ? (qv & (C - 1)) : -1;
-      hv[u] = Hdiag[jc];
-      gv[u] = G[i * ldg + jc];
-    }
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      const int a = qa[u];
-      if (a >= 0) {
-        binD[a][tid] += hv[u];     // lane-private bins: plain read-modify-write
-        binB[a][tid] += gv[u];
-        binC[a][tid] += 1;
+      for (int u = 0; u < 16; ++u) {
+        const int64_t j = j0 + tid + 64 * u;
+        const int64_t jc = (j < n) ? j : n - 1;       // clamped: the loads stay unconditional
+        const int qv = Q[i * ldq + jc];
+        qa[u] = (j < n) ? (qv & (C - 1)) : -1;
+        hv[u] = Hdiag[jc];
+        gv[u] = G[i * ldg + jc];
       }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int a = qa[u];
+        if (a >= 0) {
+          binD[a][tid] += hv[u];     // lane-private bins: plain read-modify-write
+          binB[a][tid] += gv[u];
+          binC[a][tid] += 1;
+        }
+      }
+    }
+  } else {
+    // changed columns of this row: j | old code << 16 | new code << 20 (at most fmax of them, or
+    // the sweep would not have been updated)
+    const int nf = Fcnt[i];
+    const uint32_t* __restrict__ fl = Flist + (int64_t)i * fmax;
+    for (int f = tid; f < nf; f += 64) {
+      const uint32_t e = fl[f];
+      const int64_t j = e & 0xffffu;
+      const int co = (e >> 16) & 15, cn = (e >> 20) & 15;
+      const float hv = Hdiag[j], gv = G[i * ldg + j];
+      binD[co][tid] -= hv;
+      binB[co][tid] -= gv;
+      binC[co][tid] -= 1;
+      binD[cn][tid] += hv;
+      binB[cn][tid] += gv;
+      binC[cn][tid] += 1;
     }
   }
   __syncthreads();
@@ -978,6 +1010,16 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
       sb += (double)binB[tid][l];
       c0 += binC[tid][l];
     }
+    if (from_state) {
+      sd += Vstate[(i * 2 + 0) * C + tid];
+      sb += Vstate[(i * 2 + 1) * C + tid];
+      c0 += Nstate[i * C + tid];
+    }
+    if (Vstate != nullptr) {
+      Vstate[(i * 2 + 0) * C + tid] = sd;
+      Vstate[(i * 2 + 1) * C + tid] = sb;
+      Nstate[i * C + tid] = c0;
+    }
     Dg[tid] = sd;
     rhs[tid] = sb;
     cnt[tid] = c0;
@@ -987,12 +1029,6 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
   // Off-diagonal part S_i H0 S_i^T: after a sweep that summed it, M + M^T with M the sum of the
   // per-group partial folds (coalesced reads), which also becomes the state that later sweeps
   // update; after a sweep that updated it, the state itself.
-  const bool from_state = t_use_delta(Tstat, m_rows, n, fmax);
-  if (Tlog != nullptr && i == 0 && tid == 0) {
-    Tlog[0] = from_state ? 1 : 0;
-    Tlog[1] = Tstat[0];
-    Tlog[2] = Tstat[1];
-  }
   __shared__ double Ms[16][17];
   if (!from_state) {
     const int64_t gs = mpad * C * C;
@@ -1158,6 +1194,8 @@ struct TScratch {
   int* Tstat;
   int* Cbase;           // chunks of changed columns before each row (mpad + 1)
   double* Astate;       // S_i H0 S_i^T per row, the state that later sweeps update
+  double* Vstate;       // per row and code: sum of H_jj and sum of G_ij over the code's columns
+  int* Nstate;          // per row and code: number of columns
   double* Dpart;        // one C x C slot per chunk of changed columns
   int64_t max_chunks;
   int fmax;
@@ -1195,6 +1233,8 @@ inline size_t t_layout(int64_t m, int64_t n, int nbits, char* base, TScratch* ou
   const size_t o_fc = take((size_t)mpad * sizeof(int));
   const size_t o_ts = take((8 + 3 * kTLogMax) * sizeof(int));   // counters, then (choice, max, total) per sweep
   const size_t o_as = take((size_t)mpad * C * C * sizeof(double));
+  const size_t o_vs = take((size_t)mpad * 2 * C * sizeof(double));
+  const size_t o_ns = take((size_t)mpad * C * sizeof(int));
   const size_t o_cb = take((size_t)(mpad + 1) * sizeof(int));
   // a sweep is updated only when at most m n / kDeltaInv indices changed
   const int64_t max_chunks = (m * n / kDeltaInv) / kDeltaChunk + m + 1;
@@ -1218,6 +1258,8 @@ inline size_t t_layout(int64_t m, int64_t n, int nbits, char* base, TScratch* ou
     out->Fcnt = (int*)(base + o_fc);
     out->Tstat = (int*)(base + o_ts);
     out->Astate = (double*)(base + o_as);
+    out->Vstate = (double*)(base + o_vs);
+    out->Nstate = (int*)(base + o_ns);
     out->Cbase = (int*)(base + o_cb);
     out->Dpart = (double*)(base + o_dp);
     out->max_chunks = max_chunks;
@@ -1342,7 +1384,8 @@ hipError_t launch_t_solve(hipStream_t s, const float* G, int64_t ldg, int64_t m,
   const int64_t mpad = t_mpad(m, nbits);
   int* tlog = (sweep >= 0 && sweep < kTLogMax) ? sc.Tstat + 8 + 3 * sweep : nullptr;
   hipLaunchKernelGGL(t_solve_kernel, dim3((unsigned)m), dim3(64), 0, s, sc.Apart, t_groups(n), sc.Tstat, sc.fmax,
-                     m, sc.Astate, tlog, sc.Cbase, sc.Dpart, mpad, sc.scale, sc.Hdiag, G, ldg, Q, ldq, n, nbits,
+                     m, sc.Astate, tlog, sc.Cbase, sc.Dpart, sc.Vstate, sc.Nstate, sc.Flist, sc.Fcnt, mpad, sc.scale,
+                     sc.Hdiag, G, ldg, Q, ldq, n, nbits,
                      empty_mode, T, empty_count);
   return hipGetLastError();
 }
