@@ -380,8 +380,8 @@ __global__ __launch_bounds__(256) void t_flips_kernel(const uint8_t* __restrict_
 // completed sweep has left a valid state (Tstat[2]; this kernel runs from the second sweep on).
 __global__ __launch_bounds__(1024) void t_chunks_kernel(const int* __restrict__ Fcnt, int64_t m, int fmax,
                                                         int* __restrict__ Cbase, int* __restrict__ Tstat) {
-  __shared__ int part[1024], pmax[1024], ptot[1024];
-  const int tid = threadIdx.x;
+  __shared__ int wsum[16], wmax[16], wtot[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t per = (m + 1023) / 1024;
   const int64_t b = tid * per, e = (b + per < m) ? b + per : m;
   auto chunks = [&](int c) {
@@ -395,27 +395,41 @@ __global__ __launch_bounds__(1024) void t_chunks_kernel(const int* __restrict__ 
     mx = max(mx, c);
     tot += c;
   }
-  part[tid] = s;
-  pmax[tid] = mx;
-  ptot[tid] = tot;
+  // inclusive scan of s within the wavefront, then over the 16 wavefronts
+  int incl = s;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int v = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += v;
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    mx = max(mx, __shfl_xor(mx, o, 64));
+    tot += __shfl_xor(tot, o, 64);
+  }
+  if (lane == 63) wsum[wave] = incl;
+  if (lane == 0) {
+    wmax[wave] = mx;
+    wtot[wave] = tot;
+  }
   __syncthreads();
+  int before = 0, total = 0, gmax = 0, gtot = 0;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) {
+    const int v = wsum[w];
+    if (w < wave) before += v;
+    total += v;
+    gmax = max(gmax, wmax[w]);
+    gtot += wtot[w];
+  }
   if (tid == 0) {
-    int run = 0, gmax = 0, gtot = 0;
-    for (int t = 0; t < 1024; ++t) {
-      const int v = part[t];
-      part[t] = run;
-      run += v;
-      gmax = max(gmax, pmax[t]);
-      gtot += ptot[t];
-    }
     Tstat[0] = gmax;
     Tstat[1] = gtot;
     Tstat[2] = 1;
-    Tstat[4] = run;
-    Cbase[m] = run;
+    Tstat[4] = total;
+    Cbase[m] = total;
   }
-  __syncthreads();
-  int run = part[tid];
+  int run = before + incl - s;
   for (int64_t i = b; i < e; ++i) {
     Cbase[i] = run;
     run += chunks(Fcnt[i]);
@@ -988,17 +1002,34 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
     // the sweep would not have been updated)
     const int nf = Fcnt[i];
     const uint32_t* __restrict__ fl = Flist + (int64_t)i * fmax;
-    for (int f = tid; f < nf; f += 64) {
-      const uint32_t e = fl[f];
-      const int64_t j = e & 0xffffu;
-      const int co = (e >> 16) & 15, cn = (e >> 20) & 15;
-      const float hv = Hdiag[j], gv = G[i * ldg + j];
-      binD[co][tid] -= hv;
-      binB[co][tid] -= gv;
-      binC[co][tid] -= 1;
-      binD[cn][tid] += hv;
-      binB[cn][tid] += gv;
-      binC[cn][tid] += 1;
+    // four list entries per lane are fetched together, then their eight gathered values: two
+    // round trips to memory per 256 changed columns
+    for (int f0 = 0; f0 < nf; f0 += 256) {
+      uint32_t ev[4];
+      float hv[4], gv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int f = f0 + tid + 64 * u;
+        ev[u] = fl[f < nf ? f : 0];                 // clamped: the loads stay unconditional
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int64_t j = ev[u] & 0xffffu;
+        hv[u] = Hdiag[j];
+        gv[u] = G[i * ldg + j];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (f0 + tid + 64 * u < nf) {
+          const int co = (ev[u] >> 16) & 15, cn = (ev[u] >> 20) & 15;
+          binD[co][tid] -= hv[u];
+          binB[co][tid] -= gv[u];
+          binC[co][tid] -= 1;
+          binD[cn][tid] += hv[u];
+          binB[cn][tid] += gv[u];
+          binC[cn][tid] += 1;
+        }
+      }
     }
   }
   __syncthreads();
@@ -1069,23 +1100,53 @@ __global__ __launch_bounds__(64) void t_solve_kernel(const float* __restrict__ A
     }
   }
   __syncthreads();
-  for (int e = tid; e < C * C; e += 64) {
-    const int a = e / C, b = e % C;
-    double v;
-    if (from_state) {
-      // the state of the sweep before plus this sweep's chunks of changed columns, in order
-      v = Astate[i * C * C + e];
-      const int c0 = Cbase[i], c1 = Cbase[i + 1];
-      if (c1 > c0) {
-        for (int cc = c0; cc < c1; ++cc) v += Dpart[(int64_t)cc * C * C + e];
-        Astate[i * C * C + e] = v;
-      }
-    } else {
-      v = Ms[a][b] + Ms[b][a];
-      Astate[i * C * C + e] = v;
+  if (from_state) {
+    // the state of the sweep before plus this sweep's chunks of changed columns, added in the
+    // order of the chunks; the loads of four chunks and of this thread's (up to) four entries
+    // are issued together, so a row costs one round trip to memory per four chunks
+    const int c0 = Cbase[i], c1 = Cbase[i + 1];
+    const int64_t CC = (int64_t)C * C;
+    double vv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = tid + 64 * u;
+      vv[u] = Astate[i * CC + (e < CC ? e : 0)];
     }
-    if (a == b) { v += Dg[a]; diag0[a] = v; }
-    A[a][b] = v;
+    for (int cc = c0; cc < c1; cc += 4) {
+      double t[4][4];
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int e = tid + 64 * u;
+          const bool ok = cc + w < c1 && e < CC;          // clamped address, value discarded
+          const double x = Dpart[(int64_t)(ok ? cc + w : c0) * CC + (ok ? e : 0)];
+          t[w][u] = ok ? x : 0.0;
+        }
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) vv[u] += t[w][u];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int e = tid + 64 * u;
+      if (e < CC) {
+        if (c1 > c0) Astate[i * CC + e] = vv[u];
+        const int a = e / C, b = e % C;
+        double v = vv[u];
+        if (a == b) { v += Dg[a]; diag0[a] = v; }
+        A[a][b] = v;
+      }
+    }
+  } else {
+    for (int e = tid; e < C * C; e += 64) {
+      const int a = e / C, b = e % C;
+      double v = Ms[a][b] + Ms[b][a];
+      Astate[i * C * C + e] = v;
+      if (a == b) { v += Dg[a]; diag0[a] = v; }
+      A[a][b] = v;
+    }
   }
   __syncthreads();
   // Cholesky of the non-empty principal submatrix and the two triangular solves, in registers:
