@@ -297,18 +297,47 @@ __device__ inline bool t_use_delta(const int* __restrict__ st, int64_t m, int64_
 // Zero-padded copy of Q (Qp, one byte per index, read by the fold) and, for the one-hot
 // staging of the GEMM, the byte offset of each index's entry inside the one-hot LDS tile (Qo):
 // row (i mod RW) * C + code of TK bytes, 16-byte chunks XOR-permuted by (row >> 1) & 3.
+// One thread takes 16 consecutive indices (npad is a multiple of 16): one 16-byte store of codes
+// and two of offsets; the codes come in one 16-byte load where the row of Q allows it.
 __global__ __launch_bounds__(256) void pad_q_kernel(const uint8_t* __restrict__ Q, int64_t m,
                                                     int64_t n, int64_t ldq, int64_t npad, int nbits,
-                                                    uint8_t* __restrict__ Qp,
+                                                    int vec, uint8_t* __restrict__ Qp,
                                                     uint16_t* __restrict__ Qo) {
   const int64_t i = blockIdx.y;
-  const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (k >= npad) return;
+  const int64_t k0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 16;
+  if (k0 >= npad) return;
   const int C = 1 << nbits, RW = TN >> nbits;
-  const int code = (i < m && k < n) ? (Q[i * ldq + k] & (C - 1)) : 0;
-  Qp[i * npad + k] = (uint8_t)code;
-  const int nrow = (int)(i % RW) * C + code, kk = (int)(k & (TK - 1));
-  Qo[i * npad + k] = (uint16_t)(nrow * TK + ((((kk >> 4) ^ (nrow >> 1)) & 3) << 4) + (kk & 15));
+  uint32_t w[4] = {0u, 0u, 0u, 0u};
+  if (i < m) {
+    if (vec && k0 + 16 <= n) {
+      const uint4 v = *reinterpret_cast<const uint4*>(Q + i * ldq + k0);
+      w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    } else {
+#pragma unroll
+      for (int t = 0; t < 16; ++t)
+        if (k0 + t < n) w[t >> 2] |= (uint32_t)Q[i * ldq + k0 + t] << (8 * (t & 3));
+    }
+  }
+  const uint32_t cm = (uint32_t)(C - 1) * 0x01010101u;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) w[u] &= cm;
+  *reinterpret_cast<uint4*>(Qp + i * npad + k0) = uint4{w[0], w[1], w[2], w[3]};
+  const int rbase = (int)(i % RW) * C, kc = (int)((k0 & (TK - 1)) >> 4);
+  uint32_t o[8];
+#pragma unroll
+  for (int t = 0; t < 16; t += 2) {
+    uint32_t pk = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int code = (int)((w[(t + h) >> 2] >> (8 * ((t + h) & 3))) & 0xffu);
+      const int nrow = rbase + code;
+      pk |= (uint32_t)(nrow * TK + (((kc ^ (nrow >> 1)) & 3) << 4) + (t + h)) << (16 * h);
+    }
+    o[t >> 1] = pk;
+  }
+  uint4* dst = reinterpret_cast<uint4*>(Qo + i * npad + k0);
+  dst[0] = uint4{o[0], o[1], o[2], o[3]};
+  dst[1] = uint4{o[4], o[5], o[6], o[7]};
 }
 
 // ---- changed indices of a sweep ----
@@ -1366,8 +1395,9 @@ hipError_t launch_t_pad(hipStream_t s, const uint8_t* Q, int64_t m, int64_t n, i
   TScratch sc;
   t_layout(m, n, nbits, (char*)scratch, &sc);
   const int64_t npad = t_npad(n), mpad = t_mpad(m, nbits);
-  hipLaunchKernelGGL(pad_q_kernel, dim3((unsigned)ceil_div(npad, 256), (unsigned)mpad), dim3(256), 0,
-                     s, Q, m, n, ldq, npad, nbits, sc.Qp[cur & 1], sc.Qo);
+  const int vec = ((((uintptr_t)Q) & 15) == 0 && (ldq % 16) == 0) ? 1 : 0;
+  hipLaunchKernelGGL(pad_q_kernel, dim3((unsigned)ceil_div(npad, 256 * 16), (unsigned)mpad), dim3(256), 0,
+                     s, Q, m, n, ldq, npad, nbits, vec, sc.Qp[cur & 1], sc.Qo);
   return hipGetLastError();
 }
 
