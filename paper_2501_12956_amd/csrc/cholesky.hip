@@ -22,25 +22,50 @@ __global__ void fill_i32_kernel(int* p, int v) { *p = v; }
 // W <- lower triangle of H (+ preconditioner on the diagonal), L <- 0.
 // delta (if used) must already hold the diagonal offsets.
 // thr[i] = pivot threshold of column i: tau times the diagonal entry that is factorised.
+// One thread takes four consecutive columns (16-byte loads and stores where VEC says that rows of
+// H, W and L allow them).  Entries of W right of the diagonal inside the group that holds the
+// diagonal are written as 0; the rest of the upper triangle of W is never read.
+template <bool VEC>
 __global__ __launch_bounds__(256) void copy_lower_kernel(const float* __restrict__ H, int64_t n,
                                                          int64_t ldh, float* __restrict__ W,
                                                          float* __restrict__ L, int64_t ldl,
                                                          int precond, float lambda,
                                                          const float* __restrict__ delta, float tau,
                                                          float* __restrict__ thr) {
-  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t j0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   const int64_t i = blockIdx.y;
-  if (j >= n) return;
-  L[i * ldl + j] = 0.f;
-  if (j > i) return;
-  float v = H[i * ldh + j];
-  if (j == i) {
-    if (precond == GANQ_PRECOND_LAMBDA) v += lambda;
-    if (precond == GANQ_PRECOND_DIAGDOM) v += delta[i];
-    // a diagonal that is not positive and finite fails at once (threshold +inf: no pivot passes)
-    thr[i] = (v > 0.f && v < 3.0e38f) ? tau * v : __builtin_huge_valf();
+  if (j0 >= n) return;
+  const int cnt = (int)((n - j0 < 4) ? n - j0 : 4);
+  if (VEC) {
+    *reinterpret_cast<float4*>(L + i * ldl + j0) = float4{0.f, 0.f, 0.f, 0.f};
+  } else {
+    for (int t = 0; t < cnt; ++t) L[i * ldl + j0 + t] = 0.f;
   }
-  W[i * n + j] = v;
+  if (j0 > i) return;
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  if (VEC) {
+    const float4 h = *reinterpret_cast<const float4*>(H + i * ldh + j0);
+    v[0] = h.x; v[1] = h.y; v[2] = h.z; v[3] = h.w;
+  } else {
+    for (int t = 0; t < cnt; ++t) v[t] = H[i * ldh + j0 + t];
+  }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int64_t j = j0 + t;
+    if (j > i) v[t] = 0.f;
+    if (j == i) {
+      if (precond == GANQ_PRECOND_LAMBDA) v[t] += lambda;
+      if (precond == GANQ_PRECOND_DIAGDOM) v[t] += delta[i];
+      // a diagonal that is not positive and finite fails at once (threshold +inf: no pivot passes)
+      thr[i] = (v[t] > 0.f && v[t] < 3.0e38f) ? tau * v[t] : __builtin_huge_valf();
+    }
+  }
+  if (VEC) {
+    *reinterpret_cast<float4*>(W + i * n + j0) = float4{v[0], v[1], v[2], v[3]};
+  } else {
+    for (int t = 0; t < cnt; ++t)
+      if (j0 + t <= i) W[i * n + j0 + t] = v[t];
+  }
 }
 
 // delta_i = max(sum_j |H_ij| - 2 H_ii, 1e-8), Appendix A Eq. (23); one workgroup per row.
@@ -418,8 +443,14 @@ hipError_t launch_cholesky(hipStream_t s, const float* H, int64_t n, int64_t ldh
     hipLaunchKernelGGL(diagdom_delta_kernel, dim3((unsigned)n), dim3(256), 0, s, H, n, ldh, delta);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(copy_lower_kernel, dim3((unsigned)ceil_div(n, 256), (unsigned)n), dim3(256),
-                     0, s, H, n, ldh, W, L, ldl, precond, lambda, delta, tau, thr);
+  const bool vec = (n % 4) == 0 && (ldh % 4) == 0 && (ldl % 4) == 0 && (((uintptr_t)H | (uintptr_t)L) & 15) == 0;
+  const dim3 cgrid((unsigned)ceil_div(n, 1024), (unsigned)n);
+  if (vec)
+    hipLaunchKernelGGL(copy_lower_kernel<true>, cgrid, dim3(256), 0, s, H, n, ldh, W, L, ldl, precond, lambda,
+                       delta, tau, thr);
+  else
+    hipLaunchKernelGGL(copy_lower_kernel<false>, cgrid, dim3(256), 0, s, H, n, ldh, W, L, ldl, precond, lambda,
+                       delta, tau, thr);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   for (int64_t J = 0; J < n; J += kOuter) {
     for (int64_t c0 = J; c0 < n && c0 < J + kOuter; c0 += NB) {
