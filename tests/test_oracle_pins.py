@@ -94,7 +94,9 @@ def test_diagdom_delta_formula_by_hand():
     # delta_i = max(sum_j |H_ij| - 2 H_ii, 1e-8), sum over the whole row
     expect = np.array([max(6.0 - 4.0, 1e-8), max(13.5 - 20.0, 1e-8), max(2.5 - 2.0, 1e-8)])
     Hp = ref.precondition(H, ref.PRECOND_DIAGDOM)
-    assert np.allclose(np.diag(Hp) - np.diag(H), expect)
+    assert np.array_equal(np.diag(Hp), np.diag(H) + expect)
+    # the diagonally dominant row gets the floor of Eq. (23), not zero
+    assert Hp[1, 1] == 10.0 + 1e-8 and Hp[1, 1] > 10.0
     assert np.array_equal(Hp - np.diag(np.diag(Hp)), H - np.diag(np.diag(H)))
 
 
